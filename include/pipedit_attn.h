@@ -1,0 +1,128 @@
+/*
+ * libpipedit_attn: the attention hot path of PipeDiT video-DiT inference on MI355X (gfx950).
+ *
+ * C ABI.  Every pointer is a DEVICE pointer unless the comment says "host".
+ * The caller owns every buffer; the library allocates no device memory.  All
+ * tensors are compact row-major for exactly the sizes passed:
+ *
+ *     q    [B, H, Sq,  d]  bf16        k, v [B, H, Skv, d]  bf16
+ *     out  [B, H, Sq,  d]  fp32        lse  [B, H, Sq]      fp32 (natural log)
+ *
+ * which is the head-major layout of Algorithm 1's input (Q in R^{B x h x S x D};
+ * Q[:, j, :, :] is one head).  d must be 64 or 128.  Base pointers must be
+ * 16-byte aligned.
+ *
+ * Errors: every entry point returns a pda_status; nothing throws or aborts.
+ * Arguments are validated before any device work, so the error paths can be
+ * exercised on a machine without a GPU.  pda_last_error() gives the message of
+ * the calling thread's last failure.
+ *
+ * Asynchrony: kernels are enqueued on the given hipStream_t (passed as void*;
+ * NULL is the default stream) and the call returns without waiting, except
+ * where stated.  Results are deterministic run to run (no atomics in any
+ * reduction).
+ */
+#ifndef PIPEDIT_ATTN_H
+#define PIPEDIT_ATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PDA_OK = 0,
+    PDA_ERR_INVALID_ARG = 1, /* null pointer, negative size, kv_valid_len > Skv, n < 1, ... */
+    PDA_ERR_UNSUPPORTED = 2, /* d not in {64,128}, n > PDA_MAX_PARTIALS, misaligned pointer, size overflow */
+    PDA_ERR_HIP = 3          /* a HIP runtime call failed; see pda_last_error() */
+} pda_status;
+
+#define PDA_MAX_PARTIALS 16
+
+/*
+ * Attention forward for one head group or one query range: the black-box call
+ * of Algorithm 1, step 3 (attention(Q[:,j], K[:,j], V[:,j], mask[:,j])) and of
+ * the Attention Co-processing section (Attn(Q,K,V)), taken as scaled
+ * dot-product softmax attention.  For every (b, h) and query row i:
+ *
+ *     s_j = scale * <q_i, k_j>  for j < kv_valid_len;   keys j >= kv_valid_len are hidden
+ *     lse_i = ln sum_j exp(s_j),      out_i = sum_j exp(s_j - lse_i) * v_j
+ *
+ * The mask of Algorithm 1 is reduced to that key-padding tail.  0 <=
+ * kv_valid_len <= Skv; kv_valid_len == Skv means no mask; kv_valid_len == 0
+ * writes out = 0 and lse = -inf (an empty share of the keys).  K/V rows at or
+ * beyond kv_valid_len are never read.
+ *
+ * q_offset (>= 0) is the global index of this call's first query row inside
+ * the full sequence when the call covers a query range; attention here is
+ * full (non-causal), so it does not change any value and is only validated.
+ * The caller places the range's rows by offsetting out/lse itself.
+ *
+ * Arithmetic: bf16 x bf16 products accumulated in fp32 on the matrix cores,
+ * softmax statistics in fp32, probabilities rounded to bf16 before the PV
+ * product.  Sq == 0 or B*H == 0 is a successful no-op.
+ */
+int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float* lse,
+                 int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                 int64_t kv_valid_len, int64_t q_offset, void* stream);
+
+/*
+ * Exact merge of n partial attentions computed over disjoint key sets (the
+ * recombination a Ring-Attention style key split needs, and what re-joins
+ * query ranges when each range is embedded in a full-length partial whose
+ * other rows are empty).  Per row r:
+ *
+ *     L = ln sum_p exp(lses[p][r]),   out[r,:] = sum_p exp(lses[p][r] - L) * partials[p][r,:]
+ *
+ * A partial row with lse = -inf has weight 0 and its values are never used
+ * (they may be NaN or uninitialised); if every partial is empty the row gets
+ * out = 0, lse_out = -inf.
+ *
+ * partials, lses: HOST arrays of n device pointers ([rows,d] and [rows] fp32);
+ * they are read during the call only.  out [rows,d] may alias one of the
+ * partials; lse_out [rows] is optional (NULL to skip) and may alias one of the
+ * lses.  1 <= n <= PDA_MAX_PARTIALS; d % 4 == 0, d <= 256; rows == 0 is a no-op.
+ */
+int pda_attn_merge(const float* const* partials, const float* const* lses, int n,
+                   float* out, float* lse_out, int64_t rows, int d, void* stream);
+
+/*
+ * PipeSP's head-chunk pipeline (Algorithm 1, steps 2-9) on one GPU's share of
+ * heads.  Heads are issued in order in groups of heads_per_group (the last
+ * group may be smaller; the paper uses one head per step).  For group g:
+ *
+ *   compute stream: attention over the group's heads  (step 3)
+ *   record event g on the compute stream              (step 5)
+ *   drain stream waits for event g                    (step 6)
+ *   drain stream: hand-off of the group's result      (step 7; stands in for the
+ *                 All-to-All, which needs more than one GPU: the group's slice
+ *                 of out is copied to the same slice of sink)
+ *
+ * so the hand-off of group g overlaps the attention of group g+1.  out/lse of
+ * group g are bitwise what one pda_attn_fwd call over all heads writes.
+ *
+ * sink: optional device [B,H,Sq,d] fp32 (NULL: the drain stream only waits).
+ * group_ms: optional HOST array of ceil(H/heads_per_group) floats receiving the
+ * compute-stream time of each group; total_ms: optional HOST float receiving
+ * the time from the first launch to the end of the last hand-off.  If either
+ * is non-NULL the call synchronises both streams before returning; otherwise
+ * it returns after enqueueing and the caller must wait on BOTH streams.
+ * The two streams must differ.  Events are created and destroyed inside the call.
+ */
+int pda_headchunk_run(const void* q, const void* k, const void* v, float* out, float* lse,
+                      int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                      int64_t kv_valid_len, int heads_per_group,
+                      void* compute_stream, void* drain_stream,
+                      float* sink, float* group_ms, float* total_ms);
+
+/* Message of the calling thread's most recent failure ("" if none). Never NULL. */
+const char* pda_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int pda_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEDIT_ATTN_H */

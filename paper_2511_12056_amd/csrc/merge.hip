@@ -1,0 +1,76 @@
+// Exact merge of partial attentions (per row: weights exp(lse_p - L), L = ln sum_p exp(lse_p)).
+// A streaming map bound by HBM bandwidth: every thread owns four consecutive value columns of
+// one row, reads them from each of the n partials with one 128-bit load, and writes one
+// 128-bit result.  The n log-sum-exps of the row are read by all d/4 threads of the row (one
+// cache line broadcast); the first of them also writes the merged lse.
+#include <hip/hip_runtime.h>
+#include "attn_internal.h"
+
+namespace pda {
+
+template <int N>   // N > 0: compile-time partial count; N == 0: runtime p.n
+__global__ __launch_bounds__(256) void merge_kernel(const MergeParams p, int dq /* d/4 */) {
+    const int n = N > 0 ? N : p.n;
+    const int64_t total = p.rows * dq;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = i / dq;
+        float l[16];
+        float m = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < (N > 0 ? N : 16); ++j)
+            if (j < n) {
+                l[j] = p.lse[j][row];
+                m = fmaxf(m, l[j]);
+            }
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float tot = 0.f;
+        const float msafe = (m == -INFINITY) ? 0.f : m;
+#pragma unroll
+        for (int j = 0; j < (N > 0 ? N : 16); ++j)
+            if (j < n) {
+                const float w = __expf(l[j] - msafe);      // exp(-inf) = 0 for an empty partial
+                if (w > 0.f) {                             // a weight-0 partial is never read
+                    const float4 x = reinterpret_cast<const float4*>(p.part[j])[i];
+                    acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
+                    tot += w;
+                }
+            }
+        const float inv = tot > 0.f ? 1.0f / tot : 0.f;
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+        reinterpret_cast<float4*>(p.out)[i] = acc;
+        if (p.lse_out != nullptr && i - row * dq == 0)
+            p.lse_out[row] = tot > 0.f ? msafe + __logf(tot) : -INFINITY;
+    }
+}
+
+__global__ __launch_bounds__(256) void copy_f32_kernel(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n4) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+static unsigned grid_for(int64_t items) {
+    int64_t blocks = (items + 255) / 256;
+    const int64_t cap = 256 * 32;        // 32 workgroups per CU, grid-stride beyond that
+    return (unsigned)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
+}
+
+hipError_t launch_merge(const MergeParams& p, int d, hipStream_t st) {
+    const int dq = d / 4;
+    const unsigned g = grid_for(p.rows * dq);
+    switch (p.n) {
+        case 2: hipLaunchKernelGGL(merge_kernel<2>, dim3(g), dim3(256), 0, st, p, dq); break;
+        case 3: hipLaunchKernelGGL(merge_kernel<3>, dim3(g), dim3(256), 0, st, p, dq); break;
+        case 4: hipLaunchKernelGGL(merge_kernel<4>, dim3(g), dim3(256), 0, st, p, dq); break;
+        case 8: hipLaunchKernelGGL(merge_kernel<8>, dim3(g), dim3(256), 0, st, p, dq); break;
+        default: hipLaunchKernelGGL(merge_kernel<0>, dim3(g), dim3(256), 0, st, p, dq); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t st) {
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(grid_for(n / 4)), dim3(256), 0, st,
+                       reinterpret_cast<const float4*>(src), reinterpret_cast<float4*>(dst), n / 4);
+    return hipGetLastError();
+}
+
+}  // namespace pda

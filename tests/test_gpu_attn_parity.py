@@ -1,0 +1,143 @@
+"""GPU parity of pda_attn_fwd against the fp64 oracle (element by element, through the C ABI)."""
+import numpy as np
+import pytest
+
+from synth import CONFIGS, K_ID, Q_ID, V_ID, bf16_bits_to_f32, f32_to_bf16_bits, gen_qkv, gen_tensor
+from tests.util import assert_close, gen_qkv_parallel, sample_rows, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(q, k, v, scale, n_v=None, q_offset=0):
+    import torch
+    import paper_2511_12056_amd as pda
+    B, H, Sq, d = q.shape
+    out = torch.full((B, H, Sq, d), float("nan"), device="cuda", dtype=torch.float32)
+    lse = torch.full((B, H, Sq), float("nan"), device="cuda", dtype=torch.float32)
+    pda.attn_fwd(to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(v), out, lse, scale, n_v, q_offset)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), lse.cpu().numpy()
+
+
+def _oracle(q, k, v, scale, n_v=None):
+    from oracle import attention
+    return attention(q, k, v, scale, n_v)
+
+
+def test_c1_tiny_full():
+    w = CONFIGS[1]
+    q, k, v = gen_qkv(w.seed, w.B, w.H, w.Sq, w.Skv, w.d, unit_rms=w.unit_rms)
+    o, l = _run(q, k, v, w.scale)
+    ro, rl = _oracle(q, k, v, w.scale)
+    e = assert_close(o, l, ro, rl, "C1")
+    print("C1", e)
+
+
+@pytest.mark.parametrize("B,H,Sq,Skv,d,n_v", [
+    (1, 1, 32, 64, 128, None),        # exactly one tile
+    (1, 1, 1, 1, 128, None),          # single query, single key
+    (1, 2, 700, 901, 128, 845),       # several tiles, ragged rows and keys, masked tail inside the last tile
+    (2, 3, 333, 517, 64, 500),        # batch > 1, d = 64
+    (1, 1, 257, 129, 128, 65),        # mask hides whole trailing tiles
+    (1, 2, 130, 4099, 128, 4097),     # long key axis, short query axis
+    (1, 1, 513, 64, 64, 1),           # one valid key
+])
+def test_ragged_shapes_and_masks(B, H, Sq, Skv, d, n_v):
+    q, k, v = gen_qkv(900 + Sq, B, H, Sq, Skv, d, unit_rms=False)
+    scale = d ** -0.5
+    o, l = _run(q, k, v, scale, n_v)
+    ro, rl = _oracle(q, k, v, scale, n_v)
+    assert_close(o, l, ro, rl, f"{(B, H, Sq, Skv, d, n_v)}")
+
+
+@pytest.mark.parametrize("gain", [4.0, 8.0])
+def test_peaked_scores(gain):
+    # scores with standard deviation 4-8: outputs are O(1), the running max keeps moving
+    B, H, Sq, Skv, d = 1, 2, 640, 2100, 128
+    q, k, v = gen_qkv(77, B, H, Sq, Skv, d, unit_rms=True)
+    q = f32_to_bf16_bits(bf16_bits_to_f32(q) * np.float32(gain))
+    scale = d ** -0.5
+    o, l = _run(q, k, v, scale, 2050)
+    ro, rl = _oracle(q, k, v, scale, 2050)
+    assert_close(o, l, ro, rl, f"peaked x{gain}")
+
+
+def test_scale_zero_and_empty_share():
+    q, k, v = gen_qkv(5, 1, 1, 100, 200, 128, unit_rms=False)
+    o, l = _run(q, k, v, 0.0, 150)
+    ro, rl = _oracle(q, k, v, 0.0, 150)
+    assert_close(o, l, ro, rl, "scale 0")
+    o, l = _run(q, k, v, 0.1, 0)
+    assert (o == 0).all() and np.isneginf(l).all()
+
+
+def test_hidden_keys_are_never_read():
+    B, H, Sq, Skv, d, n_v = 1, 2, 300, 777, 128, 650
+    q, k, v = gen_qkv(11, B, H, Sq, Skv, d, unit_rms=True)
+    o, l = _run(q, k, v, 0.09, n_v)
+    kp, vp = k.copy(), v.copy()
+    kp[:, :, n_v:] = 0x7FC0          # NaN payload
+    vp[:, :, n_v:] = 0x7F80          # +inf payload
+    o2, l2 = _run(q, kp, vp, 0.09, n_v)
+    assert np.array_equal(o, o2) and np.array_equal(l, l2)
+
+
+def test_q_offset_has_no_effect_and_runs_are_bitwise_reproducible():
+    q, k, v = gen_qkv(12, 1, 2, 400, 900, 128, unit_rms=True)
+    o, l = _run(q, k, v, 0.09)
+    o2, l2 = _run(q, k, v, 0.09, None, 12345)
+    assert np.array_equal(o, o2) and np.array_equal(l, l2)
+
+
+def test_query_range_call_equals_rows_of_full_call():
+    # a query range is a separate call on a row slice of q: same rows, same bits
+    q, k, v = gen_qkv(13, 1, 1, 1000, 1500, 128, unit_rms=True)
+    o, l = _run(q, k, v, 0.09)
+    a, b = 391, 777
+    o2, l2 = _run(np.ascontiguousarray(q[:, :, a:b]), k, v, 0.09, None, a)
+    assert np.array_equal(o[:, :, a:b], o2) and np.array_equal(l[:, :, a:b], l2)
+
+
+def test_invariants_on_gpu():
+    # identical V rows -> that row; zero K -> mean of V and lse = ln n
+    B, H, Sq, Skv, d = 1, 1, 200, 300, 128
+    q, k, v = gen_qkv(14, B, H, Sq, Skv, d, unit_rms=False)
+    vrow = np.tile(v[:, :, :1], (1, 1, Skv, 1))
+    o, _ = _run(q, k, vrow, 0.09)
+    # not exact on the GPU: probabilities are rounded to bf16 for the PV product while the
+    # normaliser sums them unrounded, so the weights sum to 1 only to about 2^-9 / sqrt(keys)
+    assert np.abs(o - bf16_bits_to_f32(vrow[:, :, :1])).max() < 4e-3
+    o, l = _run(q, np.zeros_like(k), v, 0.09)
+    vm = bf16_bits_to_f32(v).astype(np.float64).mean(axis=2, keepdims=True)
+    assert np.abs(o - vm).max() < 2e-3 and np.abs(l - np.log(Skv)).max() < 1e-5
+
+
+def test_c2_lowres_clip():
+    w = CONFIGS[2]
+    q, k, v = gen_qkv_parallel(w)
+    o, l = _run(q, k, v, w.scale)
+    assert np.isfinite(o).all() and np.isfinite(l).all()
+    from oracle import attention_head
+    for h in (0, 11, 23):                                   # three heads in full
+        ro, rl = attention_head(q[0, h], k[0, h], v[0, h], w.scale)
+        e = assert_close(o[0, h], l[0, h], ro, rl, f"C2 head {h}")
+        print("C2 head", h, e)
+    for h in range(w.H):                                    # every head on sampled rows
+        rows = sample_rows(w.Sq, 128, w.seed + h)
+        ro, rl = attention_head(q[0, h], k[0, h], v[0, h], w.scale, rows=rows)
+        assert_close(o[0, h][rows], l[0, h][rows], ro, rl, f"C2 head {h} sampled")
+
+
+def test_c3_masked_group_sampled_rows():
+    w = CONFIGS[3]
+    q, k, v = gen_qkv_parallel(w)
+    k[:, :, w.kv_valid_len:] = 0x7FC0                        # poison the hidden text tokens
+    v[:, :, w.kv_valid_len:] = 0x7FC0
+    o, l = _run(q, k, v, w.scale, w.kv_valid_len)
+    assert np.isfinite(o).all() and np.isfinite(l).all()
+    from oracle import attention_head
+    for h in range(w.H):
+        rows = sample_rows(w.Sq, 512, w.seed + h)
+        ro, rl = attention_head(q[0, h], k[0, h], v[0, h], w.scale, w.kv_valid_len, rows=rows)
+        e = assert_close(o[0, h][rows], l[0, h][rows], ro, rl, f"C3 head {h}")
+        print("C3 head", h, e)
