@@ -1,0 +1,152 @@
+"""Benchmark of the attention hot path at the 720p x 129-frame shape on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic Q/K/V resident in HBM:
+  1. pda_headchunk_run: 24 heads x 119 056 tokens x d=128 as 8 groups of 3 heads, two streams,
+     hand-off copy of every group's result (the PipeSP loop on one GPU's heads);
+  2. the Aco-style work split on the first 6 heads: three query ranges (40/35/25 %) as separate
+     pda_attn_fwd calls, then four key chunks as separate calls merged by pda_attn_merge.
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, qb, kb, vb, target_s=15.0):
+    """The fp64 oracle, as it stands, on a bounded row sample of head 0 against all keys."""
+    import numpy as np
+    from oracle import attention_head
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rows = np.arange(0, 256, dtype=np.int64)
+    t0 = time.perf_counter()
+    attention_head(qb[0, 0], kb[0, 0], vb[0, 0], w.scale, rows=rows)          # calibration
+    per_row = (time.perf_counter() - t0) / len(rows)
+    n = int(min(w.Sq, max(512, target_s / max(per_row, 1e-9))))
+    n = min(n, 16384)
+    rows = np.linspace(0, w.Sq - 1, n).astype(np.int64)
+    t0 = time.perf_counter()
+    attention_head(qb[0, 0], kb[0, 0], vb[0, 0], w.scale, rows=rows)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * n * w.Skv * w.d
+    return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} query rows of head 0 against all {w.Skv} keys, fp64 numpy, {dt:.1f} s",
+            "full_problem_extrapolated_s": w.flops / (flops / dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    import paper_2511_12056_amd as pda
+    from synth import CONFIGS
+    from tests.util import gen_qkv_parallel, to_dev_bf16
+
+    w, w5 = CONFIGS[4], CONFIGS[5]
+    workers = min(16, os.cpu_count() or 8)
+    qb, kb, vb = gen_qkv_parallel(w, workers=workers)
+    q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+    out = torch.empty(w.B, w.H, w.Sq, w.d, device="cuda")
+    lse = torch.empty(w.B, w.H, w.Sq, device="cuda")
+    sink = torch.empty_like(out)
+    cs, ds = torch.cuda.Stream(), torch.cuda.Stream()
+
+    # Aco-style split on the first 6 heads (views of the same tensors; B == 1 so head slices are compact)
+    H5 = w5.H
+    q5, k5, v5 = q[:, :H5], k[:, :H5], v[:, :H5]
+    out5 = torch.empty(1, H5, w.Sq, w.d, device="cuda")
+    lse5 = torch.empty(1, H5, w.Sq, device="cuda")
+    qr = [(q5[:, :, o:o + n].contiguous(), o, n) for o, n in w5.query_ranges]
+    qr_out = [(torch.empty(1, H5, n, w.d, device="cuda"), torch.empty(1, H5, n, device="cuda")) for _, _, n in qr]
+    kc = [(k5[:, :, o:o + n].contiguous(), v5[:, :, o:o + n].contiguous()) for o, n in w5.key_chunks]
+    kc_out = [(torch.empty_like(out5), torch.empty_like(lse5)) for _ in kc]
+    merge_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    split_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+
+    group_ms_all, total_ms_all = [], []
+
+    def step(i, timed):
+        gms, tms = pda.headchunk_run(q, k, v, out, lse, w.scale, w.heads_per_group, cs, ds, sink=sink, timed=True)
+        if timed:
+            group_ms_all.extend(gms); total_ms_all.append(tms)
+        with torch.cuda.stream(cs):
+            if timed: split_ev[i][0].record(cs)
+            for (qq, off, n), (oo, ll) in zip(qr, qr_out):
+                pda.attn_fwd(qq, k5, v5, oo, ll, w.scale, None, off, stream=cs)
+            for (kk, vv), (oo, ll) in zip(kc, kc_out):
+                pda.attn_fwd(q5, kk, vv, oo, ll, w.scale, None, 0, stream=cs)
+            if timed: split_ev[i][1].record(cs); merge_ev[i][0].record(cs)
+            pda.attn_merge([o for o, _ in kc_out], [l for _, l in kc_out], out5, lse5, stream=cs)
+            if timed: merge_ev[i][1].record(cs)
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    flops_chunked = float(w.flops)
+    flops_split = 2.0 * 4.0 * w.Sq * w.Skv * w.d * H5          # query-range pass + key-chunk pass
+    flops_step = flops_chunked + flops_split
+    ms_per_step = dt / args.steps * 1e3
+    value = flops_step / (dt / args.steps) * 1e-12
+
+    # dominant kernel: the attention forward; one launch = one 3-head group of the pipeline
+    launch_ms = sum(group_ms_all) / len(group_ms_all)
+    flops_launch = 4.0 * w.Sq * w.Skv * w.d * w.heads_per_group
+    achieved = flops_launch / (launch_ms * 1e-3) * 1e-12
+    merge_ms = sum(a.elapsed_time(b) for a, b in merge_ev) / args.steps
+    split_ms = sum(a.elapsed_time(b) for a, b in split_ev) / args.steps
+    n_p = len(kc)
+    merge_bytes = (n_p + 1) * (w.d + 1) * 4.0 * H5 * w.Sq
+    res = {
+        "metric": "attention TFLOP/s and % of bf16 MFMA peak at 720p x 129f latent (1 GPU)",
+        "value": value, "unit": "TFLOP/s", "pct_of_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_720p_headchunk (24 heads as 8 groups of 3, S=119056, d=128) + "
+                               "c5_720p_split_merge (6 heads: 3 query ranges, 4 key chunks + merge)",
+                   "B": w.B, "H": w.H, "d": w.d, "S": w.Sq, "heads_per_group": w.heads_per_group,
+                   "seed": w.seed, "flops_per_step": flops_step},
+        "roofline": {"kernel": "attn_fwd_kernel (one 3-head group)", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "launch_ms": launch_ms, "flops_per_launch": flops_launch, "traffic": None},
+        "roofline_merge": {"kernel": "merge_kernel<4>", "bound": "hbm", "achieved": merge_bytes / (merge_ms * 1e-3) * 1e-9,
+                           "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": merge_bytes / (merge_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS,
+                           "launch_ms": merge_ms, "bytes_per_launch": merge_bytes, "traffic": None},
+        "pipeline": {"group_ms_mean": launch_ms, "total_ms_mean": sum(total_ms_all) / len(total_ms_all),
+                     "sum_group_ms_mean": sum(group_ms_all) / args.steps, "split_pass_ms": split_ms,
+                     "chunked_tflops": flops_chunked / (sum(total_ms_all) / len(total_ms_all) * 1e-3) * 1e-12},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, qb, kb, vb)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -74,7 +74,8 @@ hipError_t launch_heads(const void* q, const void* k, const void* v, float* out,
     p.l_hs = Sq;       p.l_bs = (int64_t)H * Sq;
     p.Hg = hg;
     p.scale = scale;
-    p.scale_log2e = scale * 1.4426950408889634f;
+    // scale 0 is run with a tiny positive factor so that hidden keys (-inf scores) still get exp2(-inf) = 0
+    p.scale_log2e = std::fmax(scale * 1.4426950408889634f, 1e-37f);
     return pda::launch_attn_fwd(p, B * hg, d, attn_variant(), st);
 }
 

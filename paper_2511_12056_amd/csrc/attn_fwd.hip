@@ -29,36 +29,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "attn_internal.h"
+#include "attn_device.h"
 
 namespace pda {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-
-#define LDS_PTR(T) T __attribute__((address_space(3)))*
-
-// Lanes l and l^32 hold the two halves of one query's keys.  v_permlane32_swap hands every lane
-// both halves' values (one in each result register), so max and sum need no select.
-__device__ __forceinline__ float pair_max(float x) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float pair_sum(float x) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
-    f32x2 f = {a, b};
-    bf16x2 h = __builtin_convertvector(f, bf16x2);     // v_cvt_pk_bf16_f32, round to nearest even
-    return __builtin_bit_cast(unsigned, h);
-}
 
 template <int D, int NQ, int NW, int BN, int MINB>
 __global__ __launch_bounds__(64 * NW, MINB) void attn_fwd_kernel(const AttnParams p) {
@@ -156,6 +129,12 @@ __global__ __launch_bounds__(64 * NW, MINB) void attn_fwd_kernel(const AttnParam
 
     load_tile(0);
     store_tile(0);
+    // Pin the Q fragments as "arrived" here: otherwise the loads stay pending into the loop and the
+    // in-order memory counter makes the first MFMAs of every iteration wait for the K/V prefetch too.
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qf[nq][kk]));
     __syncthreads();
 
     for (int t = 0; t < nt; ++t) {
@@ -340,8 +319,11 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipS
     if (D == 64) return launch_variant<64, 1, 4, 64, 2>(p, BH, st);
     switch (variant) {
         case 1:  return launch_variant<128, 1, 4, 64, 2>(p, BH, st);   // M=128, two workgroups per CU
-        case 2:  return launch_variant<128, 2, 4, 64, 1>(p, BH, st);   // M=256, one wave per SIMD, 64 rows per wave
-        default: return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // M=256, two waves per SIMD
+        case 2:  return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // M=256, two waves per SIMD, phases not aligned
+        case 11: return launch_attn_fwd_pp(p, BH, 1, st);
+        case 12: return launch_attn_fwd_pp(p, BH, 2, st);
+        case 10: return launch_attn_fwd_pp(p, BH, 0, st);              // M=256, ping-pong schedule
+        default: return launch_attn_fwd_il(p, BH, st);                 // M=256, software-pipelined schedule
     }
 }
 
