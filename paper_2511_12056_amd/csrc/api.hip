@@ -4,6 +4,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
+#include <map>
+#include <mutex>
+#include <utility>
 #include <vector>
 #include "../../include/pipedit_attn.h"
 #include "attn_internal.h"
@@ -60,7 +63,7 @@ int check_attn_args(const void* q, const void* k, const void* v, const float* ou
 hipError_t launch_heads(const void* q, const void* k, const void* v, float* out, float* lse,
                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale, int64_t n_v,
                         int h0, int hg, hipStream_t st) {
-    pda::AttnParams p;
+    pda::AttnParams p{};
     p.q = static_cast<const __bf16*>(q) + (int64_t)h0 * Sq * d;
     p.k = static_cast<const __bf16*>(k) + (int64_t)h0 * Skv * d;
     p.v = static_cast<const __bf16*>(v) + (int64_t)h0 * Skv * d;
@@ -80,6 +83,35 @@ hipError_t launch_heads(const void* q, const void* k, const void* v, float* out,
 }
 
 }  // namespace
+
+namespace pda {
+
+hipError_t attn_workspace(hipStream_t st, size_t bytes, float** out) {
+    struct Buf { void* ptr; size_t size; };
+    static std::mutex mu;
+    static std::map<std::pair<int, hipStream_t>, Buf> pool;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    Buf& b = pool[{dev, st}];
+    if (b.size < bytes) {
+        if (b.ptr) {
+            // the old buffer may still be read by work queued on this stream
+            if ((e = hipStreamSynchronize(st)) != hipSuccess) return e;
+            (void)hipFree(b.ptr);
+            b.ptr = nullptr;
+            b.size = 0;
+        }
+        size_t want = bytes < (size_t)(32u << 20) ? (size_t)(32u << 20) : bytes;
+        if ((e = hipMalloc(&b.ptr, want)) != hipSuccess) return e;
+        b.size = want;
+    }
+    *out = static_cast<float*>(b.ptr);
+    return hipSuccess;
+}
+
+}  // namespace pda
 
 extern "C" {
 

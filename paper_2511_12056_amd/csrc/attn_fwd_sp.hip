@@ -1,0 +1,511 @@
+// Flash-attention forward, software-pipelined schedule for gfx950, d = 128, 64-key tiles,
+// 256 query rows per workgroup.  Template parameter NQ = number of 32-row query sub-tiles a
+// wavefront owns: NQ = 1 gives 8 wavefronts (two per SIMD), NQ = 2 gives 4 wavefronts (one per
+// SIMD, every K/V operand fragment read from LDS feeds two MFMAs).
+//
+// MFMA formulation and LDS tile layout are those of attn_fwd.hip (S^T = K Q^T, O^T = V^T P^T on
+// v_mfma_f32_32x32x16_bf16, one query per lane, XOR-swizzled 16-byte granules).  Schedule: on
+// this hardware the matrix pipe is fed through the VALU issue port (an MFMA holds it for 8 of its
+// 32 cycles, a plain VALU op for ~4, a transcendental for ~8), and the softmax of a tile needs
+// about as much port time as the tile's MFMAs need matrix-pipe time.  Each wavefront therefore
+// runs one instruction stream per key tile t that interleaves three independent pieces of work:
+//
+//     matrix pipe:   PV(t-1)  (O += V_{t-1} P_{t-1})   then   QK(t+1)  (S_{t+1} = K_{t+1} Q^T)
+//     VALU:          softmax(t):  S_t -> running max / sum, P_t (bf16)
+//     LDS reads:     MFMA operand fragments, issued PF slots ahead of their use
+//
+// written slot by slot in issue order (a scheduling barrier after every slot keeps that order).
+// The O accumulators are rescaled after the stream (PV(t-1) has to land first) and only when the
+// running max of some lane moved by more than 2^8: otherwise the old reference is kept, which is
+// exact because the final normalisation uses the same reference.  The row sum is taken over the
+// bf16-rounded probabilities (v_dot2c_f32_bf16, two per instruction), so the weights that reach
+// the PV product sum to exactly the normaliser.
+//
+// K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), four buffers per
+// tensor; the loop is unrolled four times so that every buffer offset is an immediate.  At the
+// top of iteration t a wavefront issues its share of K tile t+4 (over K tile t) and V tile t+2
+// (over V tile t-2); before the barrier that closes the iteration it waits for all but its two
+// newest batches, i.e. for K tile t+2 and V tile t, which iteration t+1 reads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "attn_internal.h"
+#include "attn_device.h"
+
+namespace pda {
+
+// 16 bytes per lane from global memory (scalar base + per-lane byte offset) straight into LDS:
+// lane l's data lands at lds_addr + 16*l (lds_addr wave-uniform, passed in M0).  Inline assembly
+// on purpose: the compiler's wait-count insertion then does not see an LDS write that it cannot
+// tell apart from the operand reads that follow (it would drain the whole prefetch before every
+// LDS read); completion is tracked by hand with s_waitcnt vmcnt before the barrier.
+__device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
+    unsigned saved_m0;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+        : "=&s"(saved_m0)
+        : "s"(lds_addr), "v"(voff), "s"(sbase)
+        : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N == 8 || N == 16 || N == 0, "add the literal below");
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+}
+
+template <int NQ>
+__global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnParams p) {
+    constexpr int D = 128;
+    constexpr int NW = 8 / NQ;            // wavefronts
+    constexpr int BN = 64;
+    constexpr int M = 256;
+    constexpr int G = D / 8;              // 16
+    constexpr int NKB = BN / 32;          // 2
+    constexpr int NKK = D / 16;           // 8
+    constexpr int NDB = D / 32;           // 4
+    constexpr int TILE = BN * D * 2;      // 16 KB
+    constexpr int NBUF = 4;
+    constexpr int K_BASE = 0, V_BASE = NBUF * TILE;       // LDS byte offsets
+    constexpr int CHUNKS = TILE / 1024;   // 16 DMA chunks of 1 KB per tile
+    constexpr int CPW = CHUNKS / NW;      // per wavefront: 2 or 4
+    constexpr int RPC = 1024 / (D * 2);   // 4 rows per chunk
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lh = lane >> 5;
+
+    // ---- work item -> (query tile, head, key range)
+    int tile = blockIdx.x, part = 0;
+    if (tile >= p.n_full && p.split > 1) {
+        const int idx = tile - p.n_full;
+        tile = p.n_full + idx / p.split;
+        part = idx - (idx / p.split) * p.split;
+    }
+    const int bh = tile / p.tiles_per_head;
+    const int q_tile = tile - bh * p.tiles_per_head;
+    const int b = bh / p.Hg, h = bh - b * p.Hg;
+    const int64_t kv0 = part * p.part_keys;            // first key of this item's range (tile aligned)
+    const int64_t kv1 = (p.split > 1 && tile >= p.n_full && kv0 + p.part_keys < p.n_v) ? kv0 + p.part_keys : p.n_v;
+    const __bf16* __restrict__ qp = p.q + (int64_t)b * p.q_bs + (int64_t)h * p.q_hs;
+    const __bf16* __restrict__ kp = p.k + (int64_t)b * p.kv_bs + (int64_t)h * p.kv_hs + kv0 * D;
+    const __bf16* __restrict__ vp = p.v + (int64_t)b * p.kv_bs + (int64_t)h * p.kv_hs + kv0 * D;
+    // part 0 writes the tile's rows of out/lse; later parts write rows 0..255 of their partial slot
+    float* __restrict__ op;
+    float* __restrict__ lp;
+    int64_t row_sub;                                   // subtracted from the global row on store
+    if (part == 0) {
+        op = p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs;
+        lp = p.lse + (int64_t)b * p.l_bs + (int64_t)h * p.l_hs;
+        row_sub = 0;
+    } else {
+        const int64_t slot = (int64_t)(tile - p.n_full) * (p.split - 1) + (part - 1);
+        op = p.part_out + slot * (M * D);
+        lp = p.part_lse + slot * M;
+        row_sub = (int64_t)q_tile * M;
+    }
+
+    const int64_t Sq = p.Sq;
+    const int n_v = (int)(kv1 - kv0);                 // keys of this item, >= 1
+    const int nt = (n_v + BN - 1) / BN;
+    const int64_t q_row0 = (int64_t)q_tile * M + wave * (32 * NQ);
+    const unsigned lds0 = (unsigned)(uintptr_t)(LDS_PTR(const void))smem;
+
+    // ---- tile DMA: wavefront w fetches the 1 KB chunks w, w+NW, ... of a tile (4 key rows each).
+    // Lane -> (row, granule to fetch); with this assignment row % 16 does not depend on the chunk
+    // number, so one per-lane offset serves all of a wavefront's chunks.
+    const int ld_row0 = wave * RPC + lane / G;        // row of chunk 0; chunk j adds j*NW*RPC
+    const int ld_gp = lane % G;                       // granule position the lane's data lands on
+    const unsigned ld_offk = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ (ld_row0 & (G - 1))) * 16);
+    const unsigned ld_offv = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ ((ld_row0 & 3) << 2)) * 16);
+    auto issue_tile = [&](const __bf16* base, unsigned off0, unsigned lds_tile, int tile) {
+        const unsigned dst = lds0 + lds_tile + wave * 1024;
+        if ((tile + 1) * BN <= n_v) {                 // whole tile valid: scalar tile base + fixed lane offsets
+            const __bf16* tbase = base + (int64_t)tile * BN * D;
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) lds_dma16(tbase, off0 + j * (NW * 1024), dst + j * (NW * 1024));
+        } else {                                      // tail or beyond: rows clamped to the last valid key
+            const int last_tile = (n_v - 1) / BN;
+            const int tb = tile < last_tile ? tile : last_tile;
+            const __bf16* tbase = base + (int64_t)tb * BN * D;
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) {
+                int row = tile * BN + ld_row0 + j * (NW * RPC);
+                row = row < n_v ? row : n_v - 1;      // hidden / out-of-range keys are never read
+                const unsigned off = (unsigned)(row - tb * BN) * (D * 2) + (off0 & (D * 2 - 1));
+                lds_dma16(tbase, off, dst + j * (NW * 1024));
+            }
+        }
+    };
+
+    // prologue: K tiles 0..3, V tiles 0..1; V buffer 3 (read by the first, all-zero-weight PV) is zeroed
+    issue_tile(kp, ld_offk, K_BASE + 0 * TILE, 0);
+    issue_tile(vp, ld_offv, V_BASE + 0 * TILE, 0);
+    issue_tile(kp, ld_offk, K_BASE + 1 * TILE, 1);
+    issue_tile(kp, ld_offk, K_BASE + 2 * TILE, 2);
+    issue_tile(kp, ld_offk, K_BASE + 3 * TILE, 3);
+    issue_tile(vp, ld_offv, V_BASE + 1 * TILE, 1);
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < TILE / 16; i += 64 * NW)
+            *reinterpret_cast<u32x4*>(smem + V_BASE + 3 * TILE + i * 16) = z;
+    }
+
+    // ---- Q operand fragments, resident for the whole sweep
+    bf16x8 qf[NQ][NKK];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        int64_t row = q_row0 + nq * 32 + li;
+        row = row < Sq ? row : Sq - 1;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+            qf[nq][kk] = *reinterpret_cast<const bf16x8*>(qp + row * D + kk * 16 + 8 * lh);
+    }
+
+    // ---- per-lane LDS operand addresses (loop invariant; buffer and block offsets are immediates)
+    // K operand: row kb*32+li, granule (2kk+lh) ^ (li % 16)
+    LDS_PTR(const unsigned char) k_ptr[NKK];
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) k_ptr[kk] = (LDS_PTR(const unsigned char))smem + (K_BASE + li * (D * 2) + (((2 * kk + lh) ^ (li & (G - 1))) * 16));
+    // V^T operand through the transposing read: within a 16-lane block, lane t supplies the address
+    // of 4 consecutive columns (t%4) of key row (t/4) and receives column t of those 4 rows.
+    const int t16 = lane & 15;
+    const int v_key_in = 4 * lh + (t16 >> 2);                  // key inside a 16-key group (first 4-key read)
+    LDS_PTR(const unsigned char) v_ptr[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+        const int g = (db * 4 + 2 * (li >> 4) + ((t16 & 3) >> 1)) ^ ((v_key_in & 3) << 2);
+        v_ptr[db] = (LDS_PTR(const unsigned char))smem + (V_BASE + v_key_in * (D * 2) + g * 16 + (t16 & 1) * 8);
+    }
+
+    float m_run[NQ], l_run[NQ];
+    f32x16 o_acc[NQ][NDB];
+    f32x16 s_a[NQ][NKB], s_b[NQ][NKB];                 // scores of two consecutive tiles, alternating roles
+    // Packed bf16 P (MFMA operand order).  One buffer serves two consecutive tiles: group (kb,u) of
+    // tile t-1 is consumed by the PV MFMAs of slots 4(2kb+u)..+3, before the softmax of tile t writes it.
+    unsigned p_io[NQ][NKB][2][4];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        m_run[nq] = -INFINITY;
+        l_run[nq] = 0.f;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o_acc[nq][db][r] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) p_io[nq][kb][u][j] = 0u;
+    }
+
+    const float c = p.scale_log2e;   // > 0 (the host substitutes a tiny positive value for scale 0)
+
+    auto mask_tail = [&](f32x16 (&s)[NQ][NKB], int t) {
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = t * BN + kb * 32 + (r >> 2) * 8 + 4 * lh + (r & 3);
+                if (key >= n_v) {
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) s[nq][kb][r] = -INFINITY;
+                }
+            }
+    };
+    auto barrier = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+
+    // Q fragments and the prologue tiles have arrived
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qf[nq][kk]));
+    wait_vmcnt<0>();
+    barrier();
+
+    // ---- S_0 = K_0 Q^T (not overlapped with anything)
+    {
+        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                const bf16x8 a = *(LDS_PTR(const bf16x8))(k_ptr[kk] + kb * 32 * (D * 2));
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq)
+                    s_a[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nq][kk], kk == 0 ? zero : s_a[nq][kb], 0, 0, 0);
+            }
+        if (BN > n_v) mask_tail(s_a, 0);
+    }
+    barrier();           // K tile 0 is overwritten by the first DMA of the loop
+
+    // One iteration; TB = t % 4 fixes every LDS buffer offset at compile time.
+    //   s_c: scores of tile t (in, overwritten by its probabilities)   s_n: scores of tile t+1 (out)
+    // Slot i (0..31) = the MFMAs fed by operand fragment i (PV fragments 0..15, then QK fragments
+    // 0..15; NQ MFMAs each), the LDS reads of fragment i+PF, and slice i of the softmax VALU work:
+    // slices 0-3 the row max, 4-5 the reference / rescale factors, 6-31 the 32 exponentials with
+    // their packing to bf16 and the row sum.
+    auto iteration = [&](auto tb_c, int t, f32x16 (&s_c)[NQ][NKB], f32x16 (&s_n)[NQ][NKB]) {
+        constexpr int TB = decltype(tb_c)::value;
+        constexpr int KN = (TB + 1) % NBUF;           // buffer of K tile t+1
+        constexpr int VP = (TB + 3) % NBUF;           // buffer of V tile t-1
+        issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);                    // over K tile t
+        issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);     // over V tile t-2
+
+        constexpr int N_PV = NKB * 2 * NDB, N_QK = NKK * NKB, N_FR = N_PV + N_QK;
+        constexpr int PF = 3, RING = 4;
+        static_assert(N_FR == 32, "slot plan below is written for d = 128 and 64-key tiles");
+        bf16x8 frag[RING];
+
+        auto load_frag = [&](auto idx) {
+            constexpr int i = decltype(idx)::value;
+            if constexpr (i < N_PV) {
+                constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
+                constexpr int off0 = VP * TILE + (kb * 32 + u * 16) * (D * 2);
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0));
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0 + 8 * (D * 2)));
+                typedef short s16x8 __attribute__((ext_vector_type(8)));
+                const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                frag[i % RING] = __builtin_bit_cast(bf16x8, av);
+            } else if constexpr (i < N_FR) {
+                constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
+                frag[i % RING] = *(LDS_PTR(const bf16x8))(k_ptr[kk] + (KN * TILE + kb * 32 * (D * 2)));
+            }
+        };
+        auto do_mfma = [&](auto idx, auto nq_c) {
+            constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
+            if constexpr (i < N_PV) {
+                constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
+                const u32x4 pv = {p_io[nq][kb][u][0], p_io[nq][kb][u][1], p_io[nq][kb][u][2], p_io[nq][kb][u][3]};
+                o_acc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], __builtin_bit_cast(bf16x8, pv),
+                                                                        o_acc[nq][db], 0, 0, 0);
+            } else {
+                constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
+                if constexpr (kk == 0) {
+                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], zero, 0, 0, 0);
+                } else {
+                    s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], s_n[nq][kb], 0, 0, 0);
+                }
+            }
+        };
+
+        // softmax state of this tile
+        float mx[NQ], m_use[NQ], alpha[NQ], mc[NQ], lsum[NQ];
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            mx[nq] = s_c[nq][0][0];
+            m_use[nq] = 0.f; alpha[nq] = 1.f; mc[nq] = 0.f; lsum[nq] = 0.f;
+        }
+        auto pack_pair = [&](auto qidx, auto nq_c) {     // pair q = elements 2q, 2q+1 of the 32 this lane holds
+            constexpr int q = decltype(qidx)::value, nq = decltype(nq_c)::value;
+            constexpr int kb = q / 8, u = (q % 8) / 4, j = q % 4;
+            const unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
+            p_io[nq][kb][u][j] = pk;
+            lsum[nq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
+                                                       __builtin_bit_cast(bf16x2, 0x3f803f80u), lsum[nq], false);
+        };
+        auto valu_slice = [&](auto idx, auto nq_c) {
+            constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
+            if constexpr (i < 4) {                                  // row max over the lane's 32 scores
+#pragma unroll
+                for (int e = 8 * i; e < 8 * i + 8; e += 2)
+                    mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 1) / 16][(e + 1) % 16]);
+            } else if constexpr (i == 4) {
+                mx[nq] = pair_max(mx[nq]);
+                // keep the old reference unless the max moved by more than 2^8 (in exp2 units)
+                const float m_new = fmaxf(m_run[nq], mx[nq]);
+                const bool move = (m_new - m_run[nq]) * c > 8.0f || m_run[nq] == -INFINITY;
+                m_use[nq] = move ? m_new : m_run[nq];
+            } else if constexpr (i == 5) {
+                alpha[nq] = m_run[nq] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_run[nq] - m_use[nq]) * c);
+                mc[nq] = m_use[nq] * c;
+            } else {                                                // 32 exponentials over 26 slots
+                constexpr int k = i - 6;
+                constexpr int h0 = k * 32 / 26, h1 = (k + 1) * 32 / 26;
+                static_for<h0, h1>([&](auto hidx) {
+                    constexpr int e = decltype(hidx)::value;
+                    if constexpr (e % 2 == 0 && e >= 2) pack_pair(std::integral_constant<int, e / 2 - 1>{}, nq_c);
+                    s_c[nq][e / 16][e % 16] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc[nq]));
+                });
+            }
+        };
+
+        // ================= interleaved region: softmax(t) | PV(t-1), QK(t+1) =================
+        static_for<0, PF>([&](auto i) { load_frag(i); });
+        static_for<0, N_FR>([&](auto idx) {
+            constexpr int i = decltype(idx)::value;
+            static_for<0, NQ>([&](auto nq_c) { do_mfma(idx, nq_c); });
+            load_frag(std::integral_constant<int, i + PF>{});
+            static_for<0, NQ>([&](auto nq_c) { valu_slice(idx, nq_c); });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, NQ>([&](auto nq_c) {
+            constexpr int nq = decltype(nq_c)::value;
+            pack_pair(std::integral_constant<int, 15>{}, nq_c);
+            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq]);
+            m_run[nq] = m_use[nq];
+        });
+        // =====================================================================================
+
+        // rescale O once PV(t-1) is in, if some lane moved its reference (rare after the first tiles)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            if (__builtin_amdgcn_ballot_w64(alpha[nq] != 1.0f) != 0) {
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o_acc[nq][db][r] *= alpha[nq];
+            }
+        }
+        if ((t + 2) * BN > n_v) mask_tail(s_n, t + 1);     // S_{t+1} holds hidden keys
+
+        if constexpr (NQ == 2) {
+            // One wavefront per SIMD owns 512 registers, half of them accumulation registers that
+            // only MFMAs (and loads) can address.  Pin what only MFMAs touch there - the O
+            // accumulators and the Q fragments - so that the VALU-visible half is left for the scores.
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) asm volatile("" : "+a"(o_acc[nq][db]));
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+a"(qf[nq][kk]));
+            }
+        }
+        wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
+        barrier();
+    };
+
+    // The loop runs over tiles 0 .. nt (the extra one only completes PV(nt-1): its scores are all
+    // hidden, so its probabilities are zero), rounded up to a multiple of four so that buffer
+    // offsets are immediates and the score / probability registers alternate roles without copies.
+    const int t_end = (nt + 4) & ~3;
+    for (int t = 0; t < t_end; t += 4) {
+        iteration(std::integral_constant<int, 0>{}, t, s_a, s_b);
+        iteration(std::integral_constant<int, 1>{}, t + 1, s_b, s_a);
+        iteration(std::integral_constant<int, 2>{}, t + 2, s_a, s_b);
+        iteration(std::integral_constant<int, 3>{}, t + 3, s_b, s_a);
+    }
+    wait_vmcnt<0>();        // no DMA may outlive the workgroup's LDS
+
+    // ---- epilogue: normalise, write out and lse
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const float l_tot = pair_sum(l_run[nq]);
+        const float inv = 1.0f / l_tot;
+        const int64_t row = q_row0 + nq * 32 + li;
+        if (row < Sq) {
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 o4 = {o_acc[nq][db][4 * a] * inv, o_acc[nq][db][4 * a + 1] * inv,
+                                o_acc[nq][db][4 * a + 2] * inv, o_acc[nq][db][4 * a + 3] * inv};
+                    *reinterpret_cast<f32x4*>(op + (row - row_sub) * D + db * 32 + a * 8 + 4 * lh) = o4;
+                }
+            if (lh == 0) lp[row - row_sub] = m_run[nq] * p.scale + __logf(l_tot);
+        }
+    }
+}
+
+// Folds the key-range partials of the cut tiles into out/lse (in place): per row,
+// L = ln sum_p exp(lse_p), out = sum_p exp(lse_p - L) out_p.  One 32-lane group per row (d = 128),
+// so a row's lse is read by all its lanes before one of them overwrites it.
+__global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int n_tail) {
+    constexpr int D = 128, M = 256;
+    const int tile = p.n_full + blockIdx.x / (M / 8);
+    const int r_in = (blockIdx.x % (M / 8)) * 8 + (threadIdx.x >> 5);
+    const int c4 = threadIdx.x & 31;
+    const int bh = tile / p.tiles_per_head;
+    const int q_tile = tile - bh * p.tiles_per_head;
+    const int b = bh / p.Hg, h = bh - b * p.Hg;
+    const int64_t row = (int64_t)q_tile * M + r_in;
+    if (row >= p.Sq) return;
+    float* op = p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D;
+    float* lp = p.lse + (int64_t)b * p.l_bs + (int64_t)h * p.l_hs + row;
+    float l[4];
+    l[0] = *lp;
+    float m = l[0];
+    for (int j = 1; j < p.split; ++j) {
+        const int64_t slot = (int64_t)(tile - p.n_full) * (p.split - 1) + (j - 1);
+        l[j] = p.part_lse[slot * M + r_in];
+        m = fmaxf(m, l[j]);
+    }
+    float4 acc = reinterpret_cast<const float4*>(op)[c4];
+    float w = __expf(l[0] - m), tot = w;
+    acc.x *= w; acc.y *= w; acc.z *= w; acc.w *= w;
+    for (int j = 1; j < p.split; ++j) {
+        const int64_t slot = (int64_t)(tile - p.n_full) * (p.split - 1) + (j - 1);
+        const float4 x = reinterpret_cast<const float4*>(p.part_out + (slot * M + r_in) * D)[c4];
+        w = __expf(l[j] - m);
+        acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
+        tot += w;
+    }
+    const float inv = 1.0f / tot;
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    reinterpret_cast<float4*>(op)[c4] = acc;
+    if (c4 == 0) *lp = m + __logf(tot);
+}
+
+template <int NQ>
+static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
+    constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
+    constexpr int M = 256, D = 128;
+    auto kern = attn_fwd_sp_kernel<NQ>;
+    static bool attr_set = false;
+    static int n_cu = 0;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        int dev = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        attr_set = true;
+    }
+    // Work plan: one workgroup per CU at a time, so tiles run in rounds of n_cu.  The tiles of the
+    // last, partly filled round are cut into `split` key ranges (as many as fit in that round, at
+    // most 4, each at least 8 key tiles long).
+    p.tiles_per_head = (int)((p.Sq + M - 1) / M);
+    const int64_t n_tiles = (int64_t)p.tiles_per_head * BH;
+    const int rem = (int)(n_tiles % n_cu);
+    int split = rem ? n_cu / rem : 1;
+    if (split > 4) split = 4;
+    while (split > 1 && p.n_v < (int64_t)split * 8 * 64) --split;
+    p.split = split;
+    p.n_full = (int)n_tiles;
+    p.part_keys = 0;
+    p.part_out = nullptr;
+    p.part_lse = nullptr;
+    int64_t items = n_tiles;
+    if (split > 1) {
+        p.n_full = (int)(n_tiles - rem);
+        p.part_keys = ((p.n_v + split - 1) / split + 63) / 64 * 64;
+        const size_t slots = (size_t)rem * (split - 1);
+        float* ws = nullptr;
+        hipError_t e = attn_workspace(st, slots * (M * D + M) * sizeof(float), &ws);
+        if (e != hipSuccess) return e;
+        p.part_out = ws;
+        p.part_lse = ws + slots * (M * D);
+        items = p.n_full + (int64_t)rem * split;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(512 / NQ), smem, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split <= 1) return e;
+    hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(rem * (M / 8))), dim3(256), 0, st, p, rem);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int nq, hipStream_t st) {
+    return nq == 2 ? launch_sp<2>(p, BH, st) : launch_sp<1>(p, BH, st);
+}
+
+}  // namespace pda

@@ -23,6 +23,17 @@ struct AttnParams {
     int Hg;                 // heads in this launch
     float scale;            // softmax scale
     float scale_log2e;      // scale * log2(e)
+    // Work items of the software-pipelined kernel (1-D grid).  Items [0, n_full) are whole 256-row
+    // query tiles (tile = item; head = tile / tiles_per_head).  Every later tile is cut into `split`
+    // key ranges of part_keys keys, one item each, so that the last, partly filled round of
+    // workgroups finishes sooner; part 0 writes out/lse, parts >= 1 write normalised partials to
+    // part_out/part_lse, which a merge pass folds into out/lse.  split <= 1: no cut.
+    int tiles_per_head;
+    int n_full;
+    int split;
+    int64_t part_keys;
+    float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
+    float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
 };
 
 // Enqueue the forward kernel for B*Hg = BH (batch, head) pairs.  variant selects a tiling (0 = default).
@@ -33,6 +44,13 @@ hipError_t launch_attn_fwd_pp(const AttnParams& p, int BH, int mode, hipStream_t
 
 // Software-pipelined kernel for d = 128 (attn_fwd_il.hip); p.n_v >= 1, p.scale_log2e > 0.
 hipError_t launch_attn_fwd_il(const AttnParams& p, int BH, hipStream_t st);
+
+// Software-pipelined kernel, four LDS buffers per tensor (attn_fwd_sp.hip); nq = 1 or 2 query sub-tiles per wavefront.
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int nq, hipStream_t st);
+
+// Device workspace of at least `bytes` bytes for work enqueued on stream st (one cached buffer per
+// stream, grown on demand; work on one stream is ordered, so consecutive launches may share it).
+hipError_t attn_workspace(hipStream_t st, size_t bytes, float** out);
 
 struct MergeParams {
     const float* part[16];
