@@ -2,8 +2,12 @@
  * libpipedit_attn: the attention hot path of PipeDiT video-DiT inference on MI355X (gfx950).
  *
  * C ABI.  Every pointer is a DEVICE pointer unless the comment says "host".
- * The caller owns every buffer; the library allocates no device memory.  All
- * tensors are compact row-major for exactly the sizes passed:
+ * The caller owns every tensor.  The library itself keeps one small cached
+ * device workspace per (device, stream) for partial results of pda_attn_fwd
+ * (32 MB unless a launch needs more; allocated on first use, kept until the
+ * process ends).  Work enqueued on one stream shares that stream's workspace,
+ * which is safe because a stream runs its work in order.  All tensors are
+ * compact row-major for exactly the sizes passed:
  *
  *     q    [B, H, Sq,  d]  bf16        k, v [B, H, Skv, d]  bf16
  *     out  [B, H, Sq,  d]  fp32        lse  [B, H, Sq]      fp32 (natural log)
@@ -81,8 +85,8 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
  *
  * partials, lses: HOST arrays of n device pointers ([rows,d] and [rows] fp32);
  * they are read during the call only.  out [rows,d] may alias one of the
- * partials; lse_out [rows] is optional (NULL to skip) and may alias one of the
- * lses.  1 <= n <= PDA_MAX_PARTIALS; d % 4 == 0, d <= 256; rows == 0 is a no-op.
+ * partials; lse_out [rows] is optional (NULL to skip) and must not alias any
+ * of the lses.  1 <= n <= PDA_MAX_PARTIALS; d % 4 == 0, d <= 256; rows == 0 is a no-op.
  */
 int pda_attn_merge(const float* const* partials, const float* const* lses, int n,
                    float* out, float* lse_out, int64_t rows, int d, void* stream);
@@ -100,7 +104,9 @@ int pda_attn_merge(const float* const* partials, const float* const* lses, int n
  *                 of out is copied to the same slice of sink)
  *
  * so the hand-off of group g overlaps the attention of group g+1.  out/lse of
- * group g are bitwise what one pda_attn_fwd call over all heads writes.
+ * group g are what one pda_attn_fwd call over the group's heads writes (a call
+ * over all heads agrees up to the rounding of probabilities: which query tiles
+ * are computed as merged key-range partials depends on the launch size).
  *
  * sink: optional device [B,H,Sq,d] fp32 (NULL: the drain stream only waits).
  * group_ms: optional HOST array of ceil(H/heads_per_group) floats receiving the

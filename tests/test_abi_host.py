@@ -1,0 +1,86 @@
+"""Host-side checks of the C ABI: the library loads, exports every declared symbol, and rejects
+bad arguments before touching the device (so these run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pda():
+    import paper_2511_12056_amd as pda
+    return pda
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pipedit_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pda_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(pda):
+    names = _declared_symbols()
+    assert names == ["pda_attn_fwd", "pda_attn_merge", "pda_headchunk_run", "pda_last_error", "pda_version"]
+    lib = C.CDLL(pda.lib_path())
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_last_error_are_callable(pda):
+    assert pda.version() >= 100
+    assert isinstance(pda.last_error(), str)
+
+
+def _fwd(pda, q=8, k=8, v=8, out=8, lse=8, B=1, H=1, Sq=8, Skv=8, d=64, scale=1.0, n_v=8, qoff=0):
+    # small integers stand in for (16-byte aligned multiples are needed: use 16*x) device addresses;
+    # every call below must fail validation before any of them is dereferenced
+    return pda.lib.pda_attn_fwd(q * 16 or None, k * 16 or None, v * 16 or None, out * 16 or None, lse * 16 or None,
+                                B, H, Sq, Skv, d, scale, n_v, qoff, None)
+
+
+def test_attn_fwd_rejects_bad_arguments(pda):
+    assert _fwd(pda, d=32) == 2 and "head dim" in pda.last_error()
+    assert _fwd(pda, n_v=9) == 1 and "kv_valid_len" in pda.last_error()
+    assert _fwd(pda, n_v=-1) == 1
+    assert _fwd(pda, Sq=-1) == 1
+    assert _fwd(pda, scale=-0.5) == 1
+    assert _fwd(pda, scale=float("nan")) == 1
+    assert _fwd(pda, q=0) == 1 and "null" in pda.last_error()
+    assert _fwd(pda, qoff=-3) == 1 and "q_offset" in pda.last_error()
+    assert _fwd(pda, B=70000, H=1) == 2
+    assert pda.lib.pda_attn_fwd(8, 16, 16, 16, 16, 1, 1, 8, 8, 64, 1.0, 8, 0, None) == 2      # misaligned q
+    # empty problems succeed without touching anything
+    assert _fwd(pda, q=0, k=0, v=0, out=0, lse=0, Sq=0) == 0
+    assert _fwd(pda, q=0, k=0, v=0, out=0, lse=0, B=0) == 0
+
+
+def test_merge_rejects_bad_arguments(pda):
+    arr = (C.c_void_p * 2)(64, 128)
+    f = pda.lib.pda_attn_merge
+    assert f(arr, arr, 0, 64, None, 4, 128, None) == 1
+    assert f(arr, arr, 17, 64, None, 4, 128, None) == 2
+    assert f(arr, arr, 2, 64, None, -1, 128, None) == 1
+    assert f(arr, arr, 2, 64, None, 4, 130, None) == 2
+    assert f(arr, arr, 2, None, None, 4, 128, None) == 1
+    assert f(None, arr, 2, 64, None, 4, 128, None) == 1
+    bad = (C.c_void_p * 2)(64, None)
+    assert f(bad, arr, 2, 64, None, 4, 128, None) == 1
+    assert f(arr, arr, 2, 64, 128, 4, 128, None) == 1 and "alias" in pda.last_error()     # lse_out == lses[1]
+    assert f(arr, arr, 2, 64, None, 0, 128, None) == 0
+
+
+def test_headchunk_rejects_bad_arguments(pda):
+    f = pda.lib.pda_headchunk_run
+    args = [16, 16, 16, 16, 16, 1, 4, 8, 8, 64, 1.0, 8]
+    assert f(*args, 0, 16, 32, None, None, None) == 1 and "heads_per_group" in pda.last_error()
+    assert f(*args, 2, 16, 16, None, None, None) == 1 and "streams" in pda.last_error()
+    assert f(*args, 2, 16, 32, 16, None, None) == 1 and "alias" in pda.last_error()      # sink == out
+    assert f(*args[:9], 48, 1.0, 8, 2, 16, 32, None, None, None) == 2
+    # an empty problem reports zero times
+    gms = (C.c_float * 2)(1.0, 1.0)
+    tot = C.c_float(1.0)
+    assert f(None, None, None, None, None, 1, 4, 0, 8, 64, 1.0, 8, 2, 16, 32, None, gms, C.byref(tot)) == 0
+    assert list(gms) == [0.0, 0.0] and tot.value == 0.0
