@@ -27,6 +27,14 @@ __device__ __forceinline__ float pair_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// max of three, as one instruction.  Written in assembly so that it stays where it is put and so
+// that no NaN-quieting copies of the operands are added (callers pass finite scores or -inf).
+__device__ __forceinline__ float max3_f32(float a, float b, float c) {
+    float r;
+    asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
     f32x2 f = {a, b};
     bf16x2 h = __builtin_convertvector(f, bf16x2);     // v_cvt_pk_bf16_f32, round to nearest even

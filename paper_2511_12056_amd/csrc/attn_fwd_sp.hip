@@ -23,7 +23,7 @@
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), four buffers per
 // tensor; the loop is unrolled four times so that every buffer offset is an immediate.  At the
-// top of iteration t a wavefront issues its share of K tile t+4 (over K tile t) and V tile t+2
+// end of iteration t a wavefront issues its share of K tile t+4 (over K tile t) and V tile t+2
 // (over V tile t-2); before the barrier that closes the iteration it waits for all but its two
 // newest batches, i.e. for K tile t+2 and V tile t, which iteration t+1 reads.
 #include <hip/hip_runtime.h>
@@ -38,13 +38,13 @@ namespace pda {
 // on purpose: the compiler's wait-count insertion then does not see an LDS write that it cannot
 // tell apart from the operand reads that follow (it would drain the whole prefetch before every
 // LDS read); completion is tracked by hand with s_waitcnt vmcnt before the barrier.
+// M0 is not restored: nothing else in this kernel uses it (LDS instructions on gfx9+ do not), and
+// the compiler is told nothing about it, so keep any M0-dependent builtin out of this file.
 __device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
-    unsigned saved_m0;
-    asm volatile(
-        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-        : "=&s"(saved_m0)
-        : "s"(lds_addr), "v"(voff), "s"(sbase)
-        : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory");
 }
 
 template <int N>
@@ -55,7 +55,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 }
 
-template <int NQ>
+template <int NQ, int OPT>
 __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnParams p) {
     constexpr int D = 128;
     constexpr int NW = 8 / NQ;            // wavefronts
@@ -122,24 +122,23 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     const int ld_gp = lane % G;                       // granule position the lane's data lands on
     const unsigned ld_offk = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ (ld_row0 & (G - 1))) * 16);
     const unsigned ld_offv = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ ((ld_row0 & 3) << 2)) * 16);
-    auto issue_tile = [&](const __bf16* base, unsigned off0, unsigned lds_tile, int tile) {
-        const unsigned dst = lds0 + lds_tile + wave * 1024;
+    // chunk j (0..CPW-1) of this wavefront's share of a tile
+    auto issue_chunk = [&](const __bf16* base, unsigned off0, unsigned lds_tile, int tile, int j) {
+        const unsigned dst = lds0 + lds_tile + wave * 1024 + j * (NW * 1024);
         if ((tile + 1) * BN <= n_v) {                 // whole tile valid: scalar tile base + fixed lane offsets
-            const __bf16* tbase = base + (int64_t)tile * BN * D;
-#pragma unroll
-            for (int j = 0; j < CPW; ++j) lds_dma16(tbase, off0 + j * (NW * 1024), dst + j * (NW * 1024));
+            lds_dma16(base + (int64_t)tile * BN * D, off0 + j * (NW * 1024), dst);
         } else {                                      // tail or beyond: rows clamped to the last valid key
             const int last_tile = (n_v - 1) / BN;
             const int tb = tile < last_tile ? tile : last_tile;
-            const __bf16* tbase = base + (int64_t)tb * BN * D;
-#pragma unroll
-            for (int j = 0; j < CPW; ++j) {
-                int row = tile * BN + ld_row0 + j * (NW * RPC);
-                row = row < n_v ? row : n_v - 1;      // hidden / out-of-range keys are never read
-                const unsigned off = (unsigned)(row - tb * BN) * (D * 2) + (off0 & (D * 2 - 1));
-                lds_dma16(tbase, off, dst + j * (NW * 1024));
-            }
+            int row = tile * BN + ld_row0 + j * (NW * RPC);
+            row = row < n_v ? row : n_v - 1;          // hidden / out-of-range keys are never read
+            const unsigned off = (unsigned)(row - tb * BN) * (D * 2) + (off0 & (D * 2 - 1));
+            lds_dma16(base + (int64_t)tb * BN * D, off, dst);
         }
+    };
+    auto issue_tile = [&](const __bf16* base, unsigned off0, unsigned lds_tile, int tile) {
+#pragma unroll
+        for (int j = 0; j < CPW; ++j) issue_chunk(base, off0, lds_tile, tile, j);
     };
 
     // prologue: K tiles 0..3, V tiles 0..1; V buffer 3 (read by the first, all-zero-weight PV) is zeroed
@@ -182,7 +181,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         v_ptr[db] = (LDS_PTR(const unsigned char))smem + (V_BASE + v_key_in * (D * 2) + g * 16 + (t16 & 1) * 8);
     }
 
-    float m_run[NQ], l_run[NQ];
+    float mc_run[NQ], l_run[NQ];     // reference max in exp2 units (max * scale * log2 e), lane's share of the running sum
     f32x16 o_acc[NQ][NDB];
     f32x16 s_a[NQ][NKB], s_b[NQ][NKB];                 // scores of two consecutive tiles, alternating roles
     // Packed bf16 P (MFMA operand order).  One buffer serves two consecutive tiles: group (kb,u) of
@@ -190,7 +189,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     unsigned p_io[NQ][NKB][2][4];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-        m_run[nq] = -INFINITY;
+        mc_run[nq] = -INFINITY;
         l_run[nq] = 0.f;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
@@ -257,9 +256,21 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         constexpr int TB = decltype(tb_c)::value;
         constexpr int KN = (TB + 1) % NBUF;           // buffer of K tile t+1
         constexpr int VP = (TB + 3) % NBUF;           // buffer of V tile t-1
-        issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);                    // over K tile t
-        issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);     // over V tile t-2
-
+        constexpr bool TWO = (OPT & 4) != 0;          // one barrier per two key tiles
+        if constexpr (TWO) {
+            // Even tile of a pair: issue the DMA of the next pair.  K tiles t+3, t+4 go over K tiles
+            // t-1, t and V tiles t+1, t+2 over V tiles t-3, t-2, all last read before the barrier
+            // that closed the previous pair; they are waited for before the barrier closing this one.
+            if constexpr (TB % 2 == 0) {
+                issue_tile(kp, ld_offk, K_BASE + ((TB + 3) % NBUF) * TILE, t + 3);
+                issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
+                issue_tile(vp, ld_offv, V_BASE + ((TB + 1) % NBUF) * TILE, t + 1);
+                issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
+            }
+        } else if constexpr ((OPT & 1) == 0) {
+            issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
+            issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
+        }
         constexpr int N_PV = NKB * 2 * NDB, N_QK = NKK * NKB, N_FR = N_PV + N_QK;
         constexpr int PF = 3, RING = 4;
         static_assert(N_FR == 32, "slot plan below is written for d = 128 and 64-key tiles");
@@ -298,43 +309,72 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             }
         };
 
-        // softmax state of this tile
-        float mx[NQ], m_use[NQ], alpha[NQ], mc[NQ], lsum[NQ];
+        // Softmax of tile t as a pipeline over the slots.  A dependent VALU instruction issues ~10
+        // cycles after its producer (13 after v_exp_f32) while independent ones issue every ~5, so
+        // every chain is split over slots: four partial maxima, then per score element e
+        //   F(e): x = s*c - mc   E(e): p = exp2(x)   C(q): pack pair q to bf16   D(q): row sum += pair
+        // one slot apart each, and two row-sum accumulators.
+        float mxj[NQ][4], mxc[NQ], mc_new[NQ], alpha[NQ], lsum[NQ][2];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
-            mx[nq] = s_c[nq][0][0];
-            m_use[nq] = 0.f; alpha[nq] = 1.f; mc[nq] = 0.f; lsum[nq] = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mxj[nq][j] = s_c[nq][j / 2][(j % 2) * 8];
+            mxc[nq] = 0.f; mc_new[nq] = 0.f; alpha[nq] = 1.f; lsum[nq][0] = 0.f; lsum[nq][1] = 0.f;
         }
-        auto pack_pair = [&](auto qidx, auto nq_c) {     // pair q = elements 2q, 2q+1 of the 32 this lane holds
-            constexpr int q = decltype(qidx)::value, nq = decltype(nq_c)::value;
-            constexpr int kb = q / 8, u = (q % 8) / 4, j = q % 4;
-            const unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
-            p_io[nq][kb][u][j] = pk;
-            lsum[nq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
-                                                       __builtin_bit_cast(bf16x2, 0x3f803f80u), lsum[nq], false);
-        };
         auto valu_slice = [&](auto idx, auto nq_c) {
             constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
-            if constexpr (i < 4) {                                  // row max over the lane's 32 scores
+            if constexpr (i < 4) {                                  // four independent max chains, 8 scores each
 #pragma unroll
-                for (int e = 8 * i; e < 8 * i + 8; e += 2)
-                    mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 1) / 16][(e + 1) % 16]);
+                for (int j = 0; j < 4; ++j) {
+                    const int e = 8 * j + 2 * i;
+                    mxj[nq][j] = max3_f32(mxj[nq][j], s_c[nq][e / 16][e % 16], s_c[nq][(e + 1) / 16][(e + 1) % 16]);
+                }
             } else if constexpr (i == 4) {
-                mx[nq] = pair_max(mx[nq]);
-                // keep the old reference unless the max moved by more than 2^8 (in exp2 units)
-                const float m_new = fmaxf(m_run[nq], mx[nq]);
-                const bool move = (m_new - m_run[nq]) * c > 8.0f || m_run[nq] == -INFINITY;
-                m_use[nq] = move ? m_new : m_run[nq];
+                float m = max3_f32(mxj[nq][0], mxj[nq][1], mxj[nq][2]);
+                m = pair_max(fmaxf(m, mxj[nq][3]));
+                mxc[nq] = m * c;
+                asm volatile("" : "+v"(mxc[nq]));
             } else if constexpr (i == 5) {
-                alpha[nq] = m_run[nq] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_run[nq] - m_use[nq]) * c);
-                mc[nq] = m_use[nq] * c;
-            } else {                                                // 32 exponentials over 26 slots
-                constexpr int k = i - 6;
-                constexpr int h0 = k * 32 / 26, h1 = (k + 1) * 32 / 26;
-                static_for<h0, h1>([&](auto hidx) {
-                    constexpr int e = decltype(hidx)::value;
-                    if constexpr (e % 2 == 0 && e >= 2) pack_pair(std::integral_constant<int, e / 2 - 1>{}, nq_c);
-                    s_c[nq][e / 16][e % 16] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc[nq]));
+                // move the reference only if the max grew by more than 2^8 (or there is none yet:
+                // -inf gives an infinite difference; a fully hidden tile gives -inf and no move)
+                mc_new[nq] = (mxc[nq] - mc_run[nq] > 8.0f) ? mxc[nq] : mc_run[nq];
+                asm volatile("" : "+v"(mc_new[nq]));
+            }
+            if constexpr (i == 8) {
+                alpha[nq] = __builtin_amdgcn_exp2f(mc_run[nq] - mc_new[nq]);      // 1 if unmoved, 0 on the first tile
+                asm volatile("" : "+v"(alpha[nq]));
+            }
+            if constexpr (i >= 6) {
+                // element e enters at slot 6 + e*22/32; stages D, C, E, F of different elements share a slot
+                static_for<0, 16>([&](auto qidx) {
+                    constexpr int q = decltype(qidx)::value;
+                    constexpr int tq = 6 + (2 * q + 1) * 22 / 32;
+                    constexpr int kb = q / 8, u = (q % 8) / 4, j = q % 4;
+                    if constexpr (tq + 3 == i) {                                   // D(q)
+                        float l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_io[nq][kb][u][j]),
+                                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), lsum[nq][q % 2], false);
+                        asm volatile("" : "+v"(l));
+                        lsum[nq][q % 2] = l;
+                    }
+                    if constexpr (tq + 2 == i) {                                   // C(q)
+                        unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
+                        asm volatile("" : "+v"(pk));
+                        p_io[nq][kb][u][j] = pk;
+                    }
+                });
+                static_for<0, 32>([&](auto eidx) {
+                    constexpr int e = decltype(eidx)::value;
+                    constexpr int te = 6 + e * 22 / 32;
+                    if constexpr (te + 1 == i) {                                   // E(e)
+                        float pe = __builtin_amdgcn_exp2f(s_c[nq][e / 16][e % 16]);
+                        asm volatile("" : "+v"(pe));
+                        s_c[nq][e / 16][e % 16] = pe;
+                    }
+                    if constexpr (te == i) {                                       // F(e)
+                        float x = __builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]);
+                        asm volatile("" : "+v"(x));
+                        s_c[nq][e / 16][e % 16] = x;
+                    }
                 });
             }
         };
@@ -343,16 +383,17 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         static_for<0, PF>([&](auto i) { load_frag(i); });
         static_for<0, N_FR>([&](auto idx) {
             constexpr int i = decltype(idx)::value;
+            if constexpr ((OPT & 2) != 0) __builtin_amdgcn_s_setprio(2);
             static_for<0, NQ>([&](auto nq_c) { do_mfma(idx, nq_c); });
+            if constexpr ((OPT & 2) != 0) __builtin_amdgcn_s_setprio(0);
             load_frag(std::integral_constant<int, i + PF>{});
             static_for<0, NQ>([&](auto nq_c) { valu_slice(idx, nq_c); });
             __builtin_amdgcn_sched_barrier(0);
         });
         static_for<0, NQ>([&](auto nq_c) {
             constexpr int nq = decltype(nq_c)::value;
-            pack_pair(std::integral_constant<int, 15>{}, nq_c);
-            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq]);
-            m_run[nq] = m_use[nq];
+            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq][0] + lsum[nq][1]);
+            mc_run[nq] = mc_new[nq];
         });
         // =====================================================================================
 
@@ -380,8 +421,22 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                 for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+a"(qf[nq][kk]));
             }
         }
-        wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
-        barrier();
+        // This iteration's DMA batch: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last
+        // read in iteration t-1).  Issued here, where the wavefronts of a workgroup arrive spread
+        // out in time, rather than right after the barrier where all of them would queue up at once.
+        if constexpr (TWO) {
+            if constexpr (TB % 2 == 1) {
+                wait_vmcnt<0>();
+                barrier();
+            }
+        } else {
+            if constexpr ((OPT & 1) == 1) {
+                issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
+                issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
+            }
+            wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
+            barrier();
+        }
     };
 
     // The loop runs over tiles 0 .. nt (the extra one only completes PV(nt-1): its scores are all
@@ -411,7 +466,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                                 o_acc[nq][db][4 * a + 2] * inv, o_acc[nq][db][4 * a + 3] * inv};
                     *reinterpret_cast<f32x4*>(op + (row - row_sub) * D + db * 32 + a * 8 + 4 * lh) = o4;
                 }
-            if (lh == 0) lp[row - row_sub] = m_run[nq] * p.scale + __logf(l_tot);
+            if (lh == 0) lp[row - row_sub] = mc_run[nq] * 0.6931471805599453f + __logf(l_tot);
         }
     }
 }
@@ -455,11 +510,11 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     if (c4 == 0) *lp = m + __logf(tot);
 }
 
-template <int NQ>
+template <int NQ, int OPT>
 static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
     constexpr int M = 256, D = 128;
-    auto kern = attn_fwd_sp_kernel<NQ>;
+    auto kern = attn_fwd_sp_kernel<NQ, OPT>;
     static bool attr_set = false;
     static int n_cu = 0;
     if (!attr_set) {
@@ -505,7 +560,11 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
 }
 
 hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int nq, hipStream_t st) {
-    return nq == 2 ? launch_sp<2>(p, BH, st) : launch_sp<1>(p, BH, st);
+    if (nq == 2) return launch_sp<2, 0>(p, BH, st);
+    if (nq == 11) return launch_sp<1, 1>(p, BH, st);
+    if (nq == 12) return launch_sp<1, 2>(p, BH, st);
+    if (nq == 14) return launch_sp<1, 4>(p, BH, st);
+    return launch_sp<1, 0>(p, BH, st);
 }
 
 }  // namespace pda
