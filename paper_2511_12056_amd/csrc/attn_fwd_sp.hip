@@ -309,72 +309,49 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             }
         };
 
-        // Softmax of tile t as a pipeline over the slots.  A dependent VALU instruction issues ~10
-        // cycles after its producer (13 after v_exp_f32) while independent ones issue every ~5, so
-        // every chain is split over slots: four partial maxima, then per score element e
-        //   F(e): x = s*c - mc   E(e): p = exp2(x)   C(q): pack pair q to bf16   D(q): row sum += pair
-        // one slot apart each, and two row-sum accumulators.
-        float mxj[NQ][4], mxc[NQ], mc_new[NQ], alpha[NQ], lsum[NQ][2];
+        // Softmax of tile t, slice by slice (anchored with empty asm statements: pure arithmetic
+        // would otherwise drift out of the slot it is written in).  Measured alternatives - four
+        // max chains, separate FMA / exp / pack / sum stages a slot apart, pre-scaled Q with
+        // exp-only slices - were not faster on this hardware and the last one costs accuracy.
+        float mx[NQ], mc_new[NQ], alpha[NQ], lsum[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) mxj[nq][j] = s_c[nq][j / 2][(j % 2) * 8];
-            mxc[nq] = 0.f; mc_new[nq] = 0.f; alpha[nq] = 1.f; lsum[nq][0] = 0.f; lsum[nq][1] = 0.f;
+            mx[nq] = s_c[nq][0][0];
+            mc_new[nq] = 0.f; alpha[nq] = 1.f; lsum[nq] = 0.f;
         }
+        auto pack_pair = [&](auto qidx, auto nq_c) {     // pair q = elements 2q, 2q+1 of the 32 this lane holds
+            constexpr int q = decltype(qidx)::value, nq = decltype(nq_c)::value;
+            constexpr int kb = q / 8, u = (q % 8) / 4, j = q % 4;
+            unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
+            asm volatile("" : "+v"(pk));
+            p_io[nq][kb][u][j] = pk;
+            // row sum over the ROUNDED probabilities, two per instruction (v_dot2c_f32_bf16)
+            lsum[nq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
+                                                       __builtin_bit_cast(bf16x2, 0x3f803f80u), lsum[nq], false);
+            asm volatile("" : "+v"(lsum[nq]));
+        };
         auto valu_slice = [&](auto idx, auto nq_c) {
             constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
-            if constexpr (i < 4) {                                  // four independent max chains, 8 scores each
+            if constexpr (i < 4) {                                  // row max over the lane's 32 scores
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int e = 8 * j + 2 * i;
-                    mxj[nq][j] = max3_f32(mxj[nq][j], s_c[nq][e / 16][e % 16], s_c[nq][(e + 1) / 16][(e + 1) % 16]);
-                }
+                for (int e = 8 * i; e < 8 * i + 8; e += 2)
+                    mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 1) / 16][(e + 1) % 16]);
             } else if constexpr (i == 4) {
-                float m = max3_f32(mxj[nq][0], mxj[nq][1], mxj[nq][2]);
-                m = pair_max(fmaxf(m, mxj[nq][3]));
-                mxc[nq] = m * c;
-                asm volatile("" : "+v"(mxc[nq]));
+                // Move the reference only if the max grew by more than 2^8 (or there is none yet:
+                // -inf gives an infinite difference; a fully hidden tile gives -inf and no move).
+                const float mxc = pair_max(mx[nq]) * c;
+                mc_new[nq] = (mxc - mc_run[nq] > 8.0f) ? mxc : mc_run[nq];
             } else if constexpr (i == 5) {
-                // move the reference only if the max grew by more than 2^8 (or there is none yet:
-                // -inf gives an infinite difference; a fully hidden tile gives -inf and no move)
-                mc_new[nq] = (mxc[nq] - mc_run[nq] > 8.0f) ? mxc[nq] : mc_run[nq];
-                asm volatile("" : "+v"(mc_new[nq]));
-            }
-            if constexpr (i == 8) {
                 alpha[nq] = __builtin_amdgcn_exp2f(mc_run[nq] - mc_new[nq]);      // 1 if unmoved, 0 on the first tile
-                asm volatile("" : "+v"(alpha[nq]));
-            }
-            if constexpr (i >= 6) {
-                // element e enters at slot 6 + e*22/32; stages D, C, E, F of different elements share a slot
-                static_for<0, 16>([&](auto qidx) {
-                    constexpr int q = decltype(qidx)::value;
-                    constexpr int tq = 6 + (2 * q + 1) * 22 / 32;
-                    constexpr int kb = q / 8, u = (q % 8) / 4, j = q % 4;
-                    if constexpr (tq + 3 == i) {                                   // D(q)
-                        float l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_io[nq][kb][u][j]),
-                                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), lsum[nq][q % 2], false);
-                        asm volatile("" : "+v"(l));
-                        lsum[nq][q % 2] = l;
-                    }
-                    if constexpr (tq + 2 == i) {                                   // C(q)
-                        unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
-                        asm volatile("" : "+v"(pk));
-                        p_io[nq][kb][u][j] = pk;
-                    }
-                });
-                static_for<0, 32>([&](auto eidx) {
-                    constexpr int e = decltype(eidx)::value;
-                    constexpr int te = 6 + e * 22 / 32;
-                    if constexpr (te + 1 == i) {                                   // E(e)
-                        float pe = __builtin_amdgcn_exp2f(s_c[nq][e / 16][e % 16]);
-                        asm volatile("" : "+v"(pe));
-                        s_c[nq][e / 16][e % 16] = pe;
-                    }
-                    if constexpr (te == i) {                                       // F(e)
-                        float x = __builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]);
-                        asm volatile("" : "+v"(x));
-                        s_c[nq][e / 16][e % 16] = x;
-                    }
+            } else {                                                // 32 exponentials over 26 slots
+                constexpr int k = i - 6;
+                constexpr int h0 = k * 32 / 26, h1 = (k + 1) * 32 / 26;
+                static_for<h0, h1>([&](auto hidx) {
+                    constexpr int e = decltype(hidx)::value;
+                    if constexpr (e % 2 == 0 && e >= 2) pack_pair(std::integral_constant<int, e / 2 - 1>{}, nq_c);
+                    float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]));
+                    asm volatile("" : "+v"(pe));
+                    s_c[nq][e / 16][e % 16] = pe;
                 });
             }
         };
@@ -392,7 +369,8 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         });
         static_for<0, NQ>([&](auto nq_c) {
             constexpr int nq = decltype(nq_c)::value;
-            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq][0] + lsum[nq][1]);
+            pack_pair(std::integral_constant<int, 15>{}, nq_c);
+            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq]);
             mc_run[nq] = mc_new[nq];
         });
         // =====================================================================================
