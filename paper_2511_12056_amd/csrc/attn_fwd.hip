@@ -323,9 +323,6 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipS
         case 11: return launch_attn_fwd_pp(p, BH, 1, st);
         case 12: return launch_attn_fwd_pp(p, BH, 2, st);
         case 21: return launch_attn_fwd_sp(p, BH, 2, st);
-        case 22: return launch_attn_fwd_sp(p, BH, 11, st);
-        case 23: return launch_attn_fwd_sp(p, BH, 12, st);
-        case 24: return launch_attn_fwd_sp(p, BH, 14, st);
         case 30: return launch_attn_fwd_il(p, BH, st);                 // three LDS buffers, runtime buffer offsets
         case 10: return launch_attn_fwd_pp(p, BH, 0, st);              // M=256, ping-pong schedule
         default: return launch_attn_fwd_sp(p, BH, 1, st);              // M=256, software-pipelined schedule

@@ -47,6 +47,15 @@ __device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff, unsi
                  : "memory");
 }
 
+// Same with the LDS address given as wave-uniform base + compile-time offset.
+template <int LDS_OFF>
+__device__ __forceinline__ void lds_dma16_at(const void* sbase, unsigned voff, unsigned lds_base) {
+    asm volatile("s_add_u32 m0, %0, %1\n\tglobal_load_lds_dwordx4 %2, %3"
+                 :
+                 : "s"(lds_base), "n"(LDS_OFF), "v"(voff), "s"(sbase)
+                 : "memory", "scc");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N == 8 || N == 16 || N == 0, "add the literal below");
@@ -55,7 +64,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 }
 
-template <int NQ, int OPT>
+template <int NQ>
 __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnParams p) {
     constexpr int D = 128;
     constexpr int NW = 8 / NQ;            // wavefronts
@@ -136,6 +145,15 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             lds_dma16(base + (int64_t)tb * BN * D, off, dst);
         }
     };
+    const unsigned dma_base = lds0 + wave * 1024;
+    unsigned ld_k[CPW], ld_v[CPW];
+#pragma unroll
+    for (int j = 0; j < CPW; ++j) {
+        ld_k[j] = ld_offk + j * (NW * 1024);
+        ld_v[j] = ld_offv + j * (NW * 1024);
+    }
+    const __bf16* k_dma = kp + 4 * BN * D;            // K tile t+4 and V tile t+2 of the coming iteration
+    const __bf16* v_dma = vp + 2 * BN * D;
     auto issue_tile = [&](const __bf16* base, unsigned off0, unsigned lds_tile, int tile) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) issue_chunk(base, off0, lds_tile, tile, j);
@@ -256,21 +274,24 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         constexpr int TB = decltype(tb_c)::value;
         constexpr int KN = (TB + 1) % NBUF;           // buffer of K tile t+1
         constexpr int VP = (TB + 3) % NBUF;           // buffer of V tile t-1
-        constexpr bool TWO = (OPT & 4) != 0;          // one barrier per two key tiles
-        if constexpr (TWO) {
-            // Even tile of a pair: issue the DMA of the next pair.  K tiles t+3, t+4 go over K tiles
-            // t-1, t and V tiles t+1, t+2 over V tiles t-3, t-2, all last read before the barrier
-            // that closed the previous pair; they are waited for before the barrier closing this one.
-            if constexpr (TB % 2 == 0) {
-                issue_tile(kp, ld_offk, K_BASE + ((TB + 3) % NBUF) * TILE, t + 3);
-                issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
-                issue_tile(vp, ld_offv, V_BASE + ((TB + 1) % NBUF) * TILE, t + 1);
-                issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
-            }
-        } else if constexpr ((OPT & 1) == 0) {
+        // DMA of this iteration: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last read
+        // in iteration t-1).  Whole tiles take the short path: running scalar tile pointers, fixed
+        // per-lane offsets, LDS destinations as immediates.
+        if ((t + 5) * BN <= n_v) {
+            static_for<0, CPW>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                lds_dma16_at<K_BASE + TB * TILE + j * (NW * 1024)>(k_dma, ld_k[j], dma_base);
+            });
+            static_for<0, CPW>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                lds_dma16_at<V_BASE + ((TB + 2) % NBUF) * TILE + j * (NW * 1024)>(v_dma, ld_v[j], dma_base);
+            });
+        } else {
             issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
             issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
         }
+        k_dma += BN * D;
+        v_dma += BN * D;
         constexpr int N_PV = NKB * 2 * NDB, N_QK = NKK * NKB, N_FR = N_PV + N_QK;
         constexpr int PF = 3, RING = 4;
         static_assert(N_FR == 32, "slot plan below is written for d = 128 and 64-key tiles");
@@ -360,9 +381,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         static_for<0, PF>([&](auto i) { load_frag(i); });
         static_for<0, N_FR>([&](auto idx) {
             constexpr int i = decltype(idx)::value;
-            if constexpr ((OPT & 2) != 0) __builtin_amdgcn_s_setprio(2);
             static_for<0, NQ>([&](auto nq_c) { do_mfma(idx, nq_c); });
-            if constexpr ((OPT & 2) != 0) __builtin_amdgcn_s_setprio(0);
             load_frag(std::integral_constant<int, i + PF>{});
             static_for<0, NQ>([&](auto nq_c) { valu_slice(idx, nq_c); });
             __builtin_amdgcn_sched_barrier(0);
@@ -402,19 +421,8 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         // This iteration's DMA batch: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last
         // read in iteration t-1).  Issued here, where the wavefronts of a workgroup arrive spread
         // out in time, rather than right after the barrier where all of them would queue up at once.
-        if constexpr (TWO) {
-            if constexpr (TB % 2 == 1) {
-                wait_vmcnt<0>();
-                barrier();
-            }
-        } else {
-            if constexpr ((OPT & 1) == 1) {
-                issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
-                issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
-            }
-            wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
-            barrier();
-        }
+        wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
+        barrier();
     };
 
     // The loop runs over tiles 0 .. nt (the extra one only completes PV(nt-1): its scores are all
@@ -488,11 +496,11 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     if (c4 == 0) *lp = m + __logf(tot);
 }
 
-template <int NQ, int OPT>
+template <int NQ>
 static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
     constexpr int M = 256, D = 128;
-    auto kern = attn_fwd_sp_kernel<NQ, OPT>;
+    auto kern = attn_fwd_sp_kernel<NQ>;
     static bool attr_set = false;
     static int n_cu = 0;
     if (!attr_set) {
@@ -538,11 +546,7 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
 }
 
 hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int nq, hipStream_t st) {
-    if (nq == 2) return launch_sp<2, 0>(p, BH, st);
-    if (nq == 11) return launch_sp<1, 1>(p, BH, st);
-    if (nq == 12) return launch_sp<1, 2>(p, BH, st);
-    if (nq == 14) return launch_sp<1, 4>(p, BH, st);
-    return launch_sp<1, 0>(p, BH, st);
+    return nq == 2 ? launch_sp<2>(p, BH, st) : launch_sp<1>(p, BH, st);
 }
 
 }  // namespace pda
