@@ -21,6 +21,18 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_720p.json")
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE runs,
+    calibrated on the hand-off copy kernel); None if no summary is there.  bench.py cannot run the
+    profiler around itself, so this is the last profiled value, with its source named."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f).get(kernel)
+    except (OSError, ValueError):
+        return None
 
 
 def cpu_baseline(w, qb, kb, vb, target_s=15.0):
@@ -132,13 +144,15 @@ def main():
                                "c5_720p_split_merge (6 heads: 3 query ranges, 4 key chunks + merge)",
                    "B": w.B, "H": w.H, "d": w.d, "S": w.Sq, "heads_per_group": w.heads_per_group,
                    "seed": w.seed, "flops_per_step": flops_step},
-        "roofline": {"kernel": "attn_fwd_kernel (one 3-head group)", "bound": "mfma", "achieved": achieved,
+        "roofline": {"kernel": "attn_fwd_sp_kernel<1> (one 3-head group)", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "launch_ms": launch_ms, "flops_per_launch": flops_launch, "traffic": None},
+                     "launch_ms": launch_ms, "flops_per_launch": flops_launch,
+                     "traffic": measured_traffic("attn_fwd_sp_kernel_3head_group")},
         "roofline_merge": {"kernel": "merge_kernel<4>", "bound": "hbm", "achieved": merge_bytes / (merge_ms * 1e-3) * 1e-9,
                            "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": merge_bytes / (merge_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS,
-                           "launch_ms": merge_ms, "bytes_per_launch": merge_bytes, "traffic": None},
+                           "launch_ms": merge_ms, "bytes_per_launch": merge_bytes,
+                           "traffic": measured_traffic("merge_kernel_4")},
         "pipeline": {"group_ms_mean": launch_ms, "total_ms_mean": sum(total_ms_all) / len(total_ms_all),
                      "sum_group_ms_mean": sum(group_ms_all) / args.steps, "split_pass_ms": split_ms,
                      "chunked_tflops": flops_chunked / (sum(total_ms_all) / len(total_ms_all) * 1e-3) * 1e-12},

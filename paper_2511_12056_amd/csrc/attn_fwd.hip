@@ -318,14 +318,9 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipS
     }
     if (D == 64) return launch_variant<64, 1, 4, 64, 2>(p, BH, st);
     switch (variant) {
-        case 1:  return launch_variant<128, 1, 4, 64, 2>(p, BH, st);   // M=128, two workgroups per CU
-        case 2:  return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // M=256, two waves per SIMD, phases not aligned
-        case 11: return launch_attn_fwd_pp(p, BH, 1, st);
-        case 12: return launch_attn_fwd_pp(p, BH, 2, st);
-        case 21: return launch_attn_fwd_sp(p, BH, 2, st);
-        case 30: return launch_attn_fwd_il(p, BH, st);                 // three LDS buffers, runtime buffer offsets
-        case 10: return launch_attn_fwd_pp(p, BH, 0, st);              // M=256, ping-pong schedule
-        default: return launch_attn_fwd_sp(p, BH, 1, st);              // M=256, software-pipelined schedule
+        case 1:  return launch_variant<128, 1, 4, 64, 2>(p, BH, st);   // reference tiling, M=128, two workgroups per CU
+        case 2:  return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // reference tiling, M=256, two waves per SIMD
+        default: return launch_attn_fwd_sp(p, BH, st);                 // software-pipelined kernel
     }
 }
 

@@ -1,7 +1,8 @@
 // Flash-attention forward, software-pipelined schedule for gfx950, d = 128, 64-key tiles,
 // 256 query rows per workgroup.  Template parameter NQ = number of 32-row query sub-tiles a
-// wavefront owns: NQ = 1 gives 8 wavefronts (two per SIMD), NQ = 2 gives 4 wavefronts (one per
-// SIMD, every K/V operand fragment read from LDS feeds two MFMAs).
+// wavefront owns.  Only NQ = 1 (8 wavefronts, two per SIMD) is instantiated: NQ = 2 (one
+// wavefront per SIMD, each K/V operand fragment feeding two MFMAs, which would halve the LDS
+// return traffic) needs more ordinary VGPRs than the 256 a wavefront can address and spills.
 //
 // MFMA formulation and LDS tile layout are those of attn_fwd.hip (S^T = K Q^T, O^T = V^T P^T on
 // v_mfma_f32_32x32x16_bf16, one query per lane, XOR-swizzled 16-byte granules).  Schedule: on
@@ -545,8 +546,8 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int nq, hipStream_t st) {
-    return nq == 2 ? launch_sp<2>(p, BH, st) : launch_sp<1>(p, BH, st);
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, hipStream_t st) {
+    return launch_sp<1>(p, BH, st);
 }
 
 }  // namespace pda

@@ -39,14 +39,8 @@ struct AttnParams {
 // Enqueue the forward kernel for B*Hg = BH (batch, head) pairs.  variant selects a tiling (0 = default).
 hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipStream_t st);
 
-// Ping-pong scheduled kernel for d = 128 (attn_fwd_pp.hip); p.n_v >= 1.
-hipError_t launch_attn_fwd_pp(const AttnParams& p, int BH, int mode, hipStream_t st);
-
-// Software-pipelined kernel for d = 128 (attn_fwd_il.hip); p.n_v >= 1, p.scale_log2e > 0.
-hipError_t launch_attn_fwd_il(const AttnParams& p, int BH, hipStream_t st);
-
-// Software-pipelined kernel, four LDS buffers per tensor (attn_fwd_sp.hip); nq = 1 or 2 query sub-tiles per wavefront.
-hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int nq, hipStream_t st);
+// Software-pipelined kernel for d = 128 (attn_fwd_sp.hip); p.n_v >= 1, p.scale_log2e > 0.
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, hipStream_t st);
 
 // Device workspace of at least `bytes` bytes for work enqueued on stream st (one cached buffer per
 // stream, grown on demand; work on one stream is ordered, so consecutive launches may share it).
