@@ -122,6 +122,90 @@ int pda_headchunk_run(const void* q, const void* k, const void* v, float* out, f
                       void* compute_stream, void* drain_stream,
                       float* sink, float* group_ms, float* total_ms);
 
+/* ---- steps next to the attention call ------------------------------------------------------ */
+
+#define PDA_MAX_LOCAL_HEADS 64
+
+/* Layouts of the hand-off target of pda_headchunk_run_ex. */
+#define PDA_SINK_HEAD_MAJOR    0  /* [B,H,Sq,d], as out (what pda_headchunk_run does) */
+#define PDA_SINK_TOKEN_ARRIVAL 1  /* [B,Sq,H,d], heads in the order PipeSP's per-head exchanges deliver them */
+#define PDA_SINK_TOKEN_FINAL   2  /* [B,Sq,H,d], heads in the original order: post-processing folded into the hand-off */
+
+/*
+ * PipeSP post-processing, Algorithm 1 steps 10-13, as one pass over the data:
+ * concat(chunks, dim=1) -> view(-1,h,n,D) -> permute(0,2,1,3) -> view(-1,h*n,D), i.e. the map
+ * Psi of the Supplement's consistency proof,
+ *
+ *     hidden[r, i*h + j, :] = chunks[j][r, i, :]      r < rows, i < n, j < h
+ *
+ * chunks: HOST array of h device pointers.  chunks[j] is what the exchange of pipeline step j
+ * delivered: [rows, n, D] fp32, one piece per source GPU i, rows = flattened (batch, local token).
+ * chunk_row_stride is the distance in floats between consecutive rows of a chunk: n*D for
+ * separate compact chunks, h*n*D when the chunks are the slices t_mod + j*n*D of one already
+ * concatenated [rows, h*n, D] tensor (head order k_mod = j*n + i).  hidden: device [rows, n*h, D]
+ * (head order k_orig = i*h + j); must not overlap any chunk.
+ * 1 <= h <= PDA_MAX_LOCAL_HEADS, n >= 1, D % 4 == 0, chunk_row_stride % 4 == 0 and >= n*D,
+ * 16-byte aligned pointers; rows == 0 is a no-op.
+ */
+int pda_pipesp_postprocess(const float* const* chunks, int h, int n, int64_t chunk_row_stride,
+                           float* hidden, int64_t rows, int D, void* stream);
+
+/*
+ * pda_headchunk_run with an explicit list of head groups and a choice of hand-off layout.
+ *
+ * group_sizes: HOST array of n_groups positive counts summing to H; group g covers the next
+ * group_sizes[g] heads (unequal groups: a head count that does not divide over the GPUs, Attention
+ * Co-processing section, last paragraph of the performance analysis).
+ *
+ * sink_layout / sp_ranks: with PDA_SINK_HEAD_MAJOR the hand-off is pda_headchunk_run's.  The two
+ * token-major layouts model the receive side of PipeSP's exchange for n = sp_ranks simulated
+ * GPUs on one device: H = n*h, global head k = i*h + j is local head j of GPU i, and the hand-off
+ * of a group writes each of its heads into sink[b, s, slot, :] with slot = j*n + i
+ * (PDA_SINK_TOKEN_ARRIVAL: the interleaved order that Algorithm 1 step 10 produces, to be fixed
+ * by pda_pipesp_postprocess with rows = B*Sq) or slot = i*h + j (PDA_SINK_TOKEN_FINAL: steps
+ * 11-13 folded into the copy).  They need sink != NULL and H % sp_ranks == 0; sp_ranks >= 1.
+ * Everything else as pda_headchunk_run; group_ms has n_groups entries.
+ */
+int pda_headchunk_run_ex(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, const int* group_sizes, int n_groups,
+                         int sp_ranks, int sink_layout,
+                         void* compute_stream, void* drain_stream,
+                         float* sink, float* group_ms, float* total_ms);
+
+/*
+ * Pre-attention pack: token-major fp32 projections x [B,S,H,d] (one row of H*d features per
+ * token) to the head-major bf16 tensor y [B,H,S,d] that Algorithm 1 slices per head.  With
+ * unit_rms != 0 every d-vector is first divided by its own root mean square (fp32 arithmetic;
+ * a zero vector stays zero).  Rounding to bf16 is to nearest even.  d must be 64 or 128;
+ * x and y 16-byte aligned and distinct; B*S*H == 0 is a no-op.
+ */
+int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, void* stream);
+
+/*
+ * Planner formulas (host only; every pointer below is a HOST pointer; no device work).
+ *
+ * pda_plan_n_decode: "Optimal GPU partitioning" of the Diffusion-VAE decoupling,
+ *     N_decode = ceil( T_decode / (T_decode + T_denoise) * N ),
+ * evaluated in double precision in that order and clamped to [1, N-1] (both groups need a GPU).
+ * Needs N >= 2 and positive finite times.
+ *
+ * pda_plan_aco: Attention Co-processing, performance analysis (Eq. 1-3),
+ *     T_baseline = t_L + t_A,  T_coop = t_L + t_A * N_denoise / (N_denoise + N_decode),
+ *     S = T_baseline / T_coop.
+ * Needs n_denoise >= 1, n_decode >= 0, t_L, t_A >= 0 and finite, t_L + t_A > 0.  Any output may be NULL.
+ *
+ * pda_plan_head_padding: heads padded to a multiple of the GPU count (same section):
+ * padded = ceil(H/n)*n, per GPU = padded/n, GPUs effectively needed = ceil(H / per GPU)
+ * (H = 24, n = 7 gives 28, 4, 6).  pda_plan_ragged_groups: the split without padding, group i
+ * gets floor(H/n) heads plus one if i < H mod n; group_sizes has n entries (zeros if H < n).
+ */
+int pda_plan_n_decode(double t_denoise, double t_decode, int N, int* n_decode);
+int pda_plan_aco(double t_L, double t_A, int n_denoise, int n_decode,
+                 double* t_baseline, double* t_coop, double* speedup);
+int pda_plan_head_padding(int H, int n_denoise, int* padded_heads, int* heads_per_gpu, int* gpus_needed);
+int pda_plan_ragged_groups(int H, int n, int* group_sizes);
+
 /* Message of the calling thread's most recent failure ("" if none). Never NULL. */
 const char* pda_last_error(void);
 

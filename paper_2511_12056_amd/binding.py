@@ -14,6 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "libpipedit_attn.so")
 
 PDA_OK, PDA_ERR_INVALID_ARG, PDA_ERR_UNSUPPORTED, PDA_ERR_HIP = 0, 1, 2, 3
 PDA_MAX_PARTIALS = 16
+PDA_MAX_LOCAL_HEADS = 64
+PDA_SINK_HEAD_MAJOR, PDA_SINK_TOKEN_ARRIVAL, PDA_SINK_TOKEN_FINAL = 0, 1, 2
 
 
 class PdaError(RuntimeError):
@@ -40,6 +42,22 @@ def _load() -> C.CDLL:
     lib.pda_headchunk_run.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i32, vp, vp, fp,
                                       C.POINTER(f32), C.POINTER(f32)]
     lib.pda_headchunk_run.restype = i32
+    lib.pda_headchunk_run_ex.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, C.POINTER(i32), i32,
+                                         i32, i32, vp, vp, fp, C.POINTER(f32), C.POINTER(f32)]
+    lib.pda_headchunk_run_ex.restype = i32
+    lib.pda_pipesp_postprocess.argtypes = [C.POINTER(vp), i32, i32, i64, fp, i64, i32, vp]
+    lib.pda_pipesp_postprocess.restype = i32
+    lib.pda_pack_heads.argtypes = [fp, vp, i32, i64, i32, i32, i32, vp]
+    lib.pda_pack_heads.restype = i32
+    f64 = C.c_double
+    lib.pda_plan_n_decode.argtypes = [f64, f64, i32, C.POINTER(i32)]
+    lib.pda_plan_n_decode.restype = i32
+    lib.pda_plan_aco.argtypes = [f64, f64, i32, i32, C.POINTER(f64), C.POINTER(f64), C.POINTER(f64)]
+    lib.pda_plan_aco.restype = i32
+    lib.pda_plan_head_padding.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+    lib.pda_plan_head_padding.restype = i32
+    lib.pda_plan_ragged_groups.argtypes = [i32, i32, C.POINTER(i32)]
+    lib.pda_plan_ragged_groups.restype = i32
     lib.pda_last_error.argtypes = []
     lib.pda_last_error.restype = C.c_char_p
     lib.pda_version.argtypes = []
@@ -143,3 +161,94 @@ def headchunk_run(q, k, v, out, lse, scale: float, heads_per_group: int, compute
     if timed:
         return [gms[i] for i in range(n_groups)], tms.value
     return None
+
+
+def headchunk_run_ex(q, k, v, out, lse, scale: float, group_sizes: Sequence[int], compute_stream, drain_stream,
+                     kv_valid_len: Optional[int] = None, sink=None, sp_ranks: int = 1,
+                     sink_layout: int = PDA_SINK_HEAD_MAJOR, timed: bool = False):
+    """pda_headchunk_run_ex.  sink is [B,H,Sq,d] (head-major layout) or [B,Sq,H,d] (token-major layouts)."""
+    import torch
+    B, H, Sq, d = q.shape
+    Skv = k.shape[2]
+    _expect(q, torch.bfloat16, (B, H, Sq, d), "q")
+    _expect(k, torch.bfloat16, (B, H, Skv, d), "k")
+    _expect(v, torch.bfloat16, (B, H, Skv, d), "v")
+    _expect(out, torch.float32, (B, H, Sq, d), "out")
+    _expect(lse, torch.float32, (B, H, Sq), "lse")
+    if sink is not None:
+        _expect(sink, torch.float32, (B, H, Sq, d) if sink_layout == PDA_SINK_HEAD_MAJOR else (B, Sq, H, d), "sink")
+    n_v = Skv if kv_valid_len is None else int(kv_valid_len)
+    n_groups = len(group_sizes)
+    sizes = (C.c_int * max(n_groups, 1))(*[int(x) for x in group_sizes])
+    gms = (C.c_float * max(n_groups, 1))() if timed else None
+    tms = C.c_float(0.0) if timed else None
+    _check(lib.pda_headchunk_run_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
+                                    n_v, sizes, n_groups, int(sp_ranks), int(sink_layout),
+                                    _stream_handle(compute_stream), _stream_handle(drain_stream), _ptr(sink),
+                                    gms if timed else None, C.byref(tms) if timed else None))
+    if timed:
+        return [gms[i] for i in range(n_groups)], tms.value
+    return None
+
+
+def pipesp_postprocess(chunks: Sequence, h: int, n: int, hidden, chunk_row_stride: Optional[int] = None, stream=None):
+    """pda_pipesp_postprocess: h chunks [rows,n,D] fp32 -> hidden [rows,n*h,D] fp32.
+
+    chunks may also be ONE concatenated tensor [rows,h*n,D]; its h slices are then passed with the
+    concatenated tensor's row stride.
+    """
+    import torch
+    rows, HH, D = hidden.shape
+    if HH != h * n:
+        raise ValueError("hidden: middle axis must be n*h")
+    _expect(hidden, torch.float32, (rows, h * n, D), "hidden")
+    if hasattr(chunks, "data_ptr"):
+        _expect(chunks, torch.float32, (rows, h * n, D), "t_mod")
+        ptrs = [chunks.data_ptr() + j * n * D * 4 for j in range(h)]
+        stride = h * n * D if chunk_row_stride is None else int(chunk_row_stride)
+    else:
+        if len(chunks) != h:
+            raise ValueError("need h chunks")
+        for j, c in enumerate(chunks):
+            _expect(c, torch.float32, (rows, n, D), f"chunk {j}")
+        ptrs = [c.data_ptr() for c in chunks]
+        stride = n * D if chunk_row_stride is None else int(chunk_row_stride)
+    arr = (C.c_void_p * max(h, 1))(*ptrs)
+    _check(lib.pda_pipesp_postprocess(arr, int(h), int(n), stride, _ptr(hidden), rows, D, _stream_handle(stream)))
+    return hidden
+
+
+def pack_heads(x, y, unit_rms: bool, stream=None):
+    """pda_pack_heads: x [B,S,H,d] fp32 -> y [B,H,S,d] bf16."""
+    import torch
+    B, S, H, d = x.shape
+    _expect(x, torch.float32, (B, S, H, d), "x")
+    _expect(y, torch.bfloat16, (B, H, S, d), "y")
+    _check(lib.pda_pack_heads(_ptr(x), _ptr(y), B, S, H, d, 1 if unit_rms else 0, _stream_handle(stream)))
+    return y
+
+
+def plan_n_decode(t_denoise: float, t_decode: float, N: int) -> int:
+    out = C.c_int(0)
+    _check(lib.pda_plan_n_decode(float(t_denoise), float(t_decode), int(N), C.byref(out)))
+    return out.value
+
+
+def plan_aco(t_L: float, t_A: float, n_denoise: int, n_decode: int):
+    """(T_baseline, T_coop, speed-up S)."""
+    a, b, c = C.c_double(0), C.c_double(0), C.c_double(0)
+    _check(lib.pda_plan_aco(float(t_L), float(t_A), int(n_denoise), int(n_decode), C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def plan_head_padding(H: int, n_denoise: int):
+    """(padded heads, heads per GPU, GPUs effectively needed)."""
+    a, b, c = C.c_int(0), C.c_int(0), C.c_int(0)
+    _check(lib.pda_plan_head_padding(int(H), int(n_denoise), C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def plan_ragged_groups(H: int, n: int):
+    arr = (C.c_int * max(int(n), 1))()
+    _check(lib.pda_plan_ragged_groups(int(H), int(n), arr))
+    return [arr[i] for i in range(int(n))]

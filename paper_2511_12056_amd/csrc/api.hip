@@ -82,6 +82,89 @@ hipError_t launch_heads(const void* q, const void* k, const void* v, float* out,
     return pda::launch_attn_fwd(p, B * hg, d, attn_variant(), st);
 }
 
+// The head-chunk pipeline (Algorithm 1, steps 2-9) over the given groups; arguments already validated.
+int run_pipeline(const void* q, const void* k, const void* v, float* out, float* lse,
+                 int B, int H, int64_t Sq, int64_t Skv, int d, float scale, int64_t kv_valid_len,
+                 const std::vector<int>& sizes, int sp_ranks, int sink_layout,
+                 void* compute_stream, void* drain_stream, float* sink, float* group_ms, float* total_ms) {
+    if (compute_stream == drain_stream) return fail(PDA_ERR_INVALID_ARG, "compute and drain streams must differ");
+    if (sink && !aligned16(sink)) return fail(PDA_ERR_UNSUPPORTED, "sink must be 16-byte aligned");
+    if (sink && sink == out) return fail(PDA_ERR_INVALID_ARG, "sink must not alias out");
+    const int n_groups = (int)sizes.size();
+    if (B == 0 || H == 0 || Sq == 0) {
+        if (total_ms) *total_ms = 0.f;
+        for (int g = 0; group_ms && g < n_groups; ++g) group_ms[g] = 0.f;
+        return PDA_OK;
+    }
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream), ds = static_cast<hipStream_t>(drain_stream);
+    const bool timed = group_ms != nullptr || total_ms != nullptr;
+
+    // Events: done[g] orders the hand-off of group g after its attention (Algorithm 1, steps 5-6);
+    // beg[g]/done[g] also time the group when timing is requested.
+    std::vector<hipEvent_t> done(n_groups, nullptr), beg(timed ? n_groups : 0, nullptr);
+    hipEvent_t drain_end = nullptr;
+    hipError_t e = hipSuccess;
+    const unsigned flags = timed ? hipEventDefault : hipEventDisableTiming;
+    auto cleanup = [&]() {
+        for (auto ev : done) if (ev) (void)hipEventDestroy(ev);
+        for (auto ev : beg) if (ev) (void)hipEventDestroy(ev);
+        if (drain_end) (void)hipEventDestroy(drain_end);
+    };
+    for (int g = 0; g < n_groups && e == hipSuccess; ++g) {
+        e = hipEventCreateWithFlags(&done[g], flags);
+        if (e == hipSuccess && timed) e = hipEventCreateWithFlags(&beg[g], hipEventDefault);
+    }
+    if (e == hipSuccess && timed) e = hipEventCreateWithFlags(&drain_end, hipEventDefault);
+    if (e != hipSuccess) { cleanup(); return hip_fail(e, "event creation"); }
+
+    const int h_local = H / sp_ranks;
+    for (int g = 0, h0 = 0; g < n_groups; h0 += sizes[g], ++g) {
+        const int hg = sizes[g];
+        if (timed && (e = hipEventRecord(beg[g], cs)) != hipSuccess) break;
+        if ((e = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, h0, hg, cs)) != hipSuccess) break;
+        if ((e = hipEventRecord(done[g], cs)) != hipSuccess) break;
+        if ((e = hipStreamWaitEvent(ds, done[g], 0)) != hipSuccess) break;
+        if (sink) {
+            // hand-off of this group's result (step 7): its slice of out goes to the same slice of
+            // sink, or into the token-major buffer at the head slots the layout asks for
+            for (int b = 0; b < B && e == hipSuccess; ++b) {
+                const int64_t off = ((int64_t)b * H + h0) * Sq * d;
+                if (sink_layout == PDA_SINK_HEAD_MAJOR)
+                    e = pda::launch_copy_f32(out + off, sink + off, (int64_t)hg * Sq * d, ds);
+                else
+                    e = pda::launch_scatter_heads(out + off, sink + (int64_t)b * Sq * H * d, Sq, d, hg, H, h0, h_local,
+                                                  sp_ranks, sink_layout == PDA_SINK_TOKEN_ARRIVAL, ds);
+            }
+            if (e != hipSuccess) break;
+        }
+    }
+    if (e == hipSuccess && timed) e = hipEventRecord(drain_end, ds);
+    if (e != hipSuccess) {
+        (void)hipStreamSynchronize(cs);
+        (void)hipStreamSynchronize(ds);
+        cleanup();
+        return hip_fail(e, "head-chunk pipeline");
+    }
+    if (timed) {
+        if ((e = hipStreamSynchronize(cs)) == hipSuccess) e = hipStreamSynchronize(ds);
+        float ms = 0.f;
+        for (int g = 0; g < n_groups && e == hipSuccess; ++g) {
+            e = hipEventElapsedTime(&ms, beg[g], done[g]);
+            if (group_ms) group_ms[g] = ms;
+        }
+        if (e == hipSuccess && total_ms) {
+            e = hipEventElapsedTime(&ms, beg[0], drain_end);
+            *total_ms = ms;
+        }
+        cleanup();
+        if (e != hipSuccess) return hip_fail(e, "head-chunk timing");
+        return PDA_OK;
+    }
+    // Untimed: destroying a recorded event is allowed; its resources are released once it completes.
+    cleanup();
+    return PDA_OK;
+}
+
 }  // namespace
 
 namespace pda {
@@ -117,7 +200,7 @@ extern "C" {
 
 const char* pda_last_error(void) { return g_err; }
 
-int pda_version(void) { return 100; }
+int pda_version(void) { return 200; }
 
 int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float* lse,
                  int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
@@ -169,76 +252,126 @@ int pda_headchunk_run(const void* q, const void* k, const void* v, float* out, f
     int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len);
     if (rc != PDA_OK) return rc;
     if (heads_per_group < 1) return fail(PDA_ERR_INVALID_ARG, "heads_per_group=%d (need >= 1)", heads_per_group);
-    if (compute_stream == drain_stream) return fail(PDA_ERR_INVALID_ARG, "compute and drain streams must differ");
-    if (sink && !aligned16(sink)) return fail(PDA_ERR_UNSUPPORTED, "sink must be 16-byte aligned");
-    if (sink && sink == out) return fail(PDA_ERR_INVALID_ARG, "sink must not alias out");
-    const int n_groups = H > 0 ? (H + heads_per_group - 1) / heads_per_group : 0;
-    if (B == 0 || H == 0 || Sq == 0) {
-        if (total_ms) *total_ms = 0.f;
-        for (int g = 0; group_ms && g < n_groups; ++g) group_ms[g] = 0.f;
-        return PDA_OK;
-    }
-    hipStream_t cs = static_cast<hipStream_t>(compute_stream), ds = static_cast<hipStream_t>(drain_stream);
-    const bool timed = group_ms != nullptr || total_ms != nullptr;
+    std::vector<int> sizes;
+    for (int h0 = 0; h0 < H; h0 += heads_per_group) sizes.push_back(h0 + heads_per_group <= H ? heads_per_group : H - h0);
+    return run_pipeline(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, sizes, 1, PDA_SINK_HEAD_MAJOR,
+                        compute_stream, drain_stream, sink, group_ms, total_ms);
+}
 
-    // Events: done[g] orders the hand-off of group g after its attention (Algorithm 1, steps 5-6);
-    // beg[g]/done[g] also time the group when timing is requested.
-    std::vector<hipEvent_t> done(n_groups, nullptr), beg(timed ? n_groups : 0, nullptr);
-    hipEvent_t drain_end = nullptr;
-    hipError_t e = hipSuccess;
-    const unsigned flags = timed ? hipEventDefault : hipEventDisableTiming;
-    auto cleanup = [&]() {
-        for (auto ev : done) if (ev) (void)hipEventDestroy(ev);
-        for (auto ev : beg) if (ev) (void)hipEventDestroy(ev);
-        if (drain_end) (void)hipEventDestroy(drain_end);
-    };
-    for (int g = 0; g < n_groups && e == hipSuccess; ++g) {
-        e = hipEventCreateWithFlags(&done[g], flags);
-        if (e == hipSuccess && timed) e = hipEventCreateWithFlags(&beg[g], hipEventDefault);
-    }
-    if (e == hipSuccess && timed) e = hipEventCreateWithFlags(&drain_end, hipEventDefault);
-    if (e != hipSuccess) { cleanup(); return hip_fail(e, "event creation"); }
-
+int pda_headchunk_run_ex(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, const int* group_sizes, int n_groups,
+                         int sp_ranks, int sink_layout,
+                         void* compute_stream, void* drain_stream,
+                         float* sink, float* group_ms, float* total_ms) {
+    int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len);
+    if (rc != PDA_OK) return rc;
+    if (n_groups < 0 || (n_groups > 0 && !group_sizes)) return fail(PDA_ERR_INVALID_ARG, "bad group list (n_groups=%d)", n_groups);
+    int64_t sum = 0;
     for (int g = 0; g < n_groups; ++g) {
-        const int h0 = g * heads_per_group;
-        const int hg = (h0 + heads_per_group <= H) ? heads_per_group : H - h0;
-        if (timed && (e = hipEventRecord(beg[g], cs)) != hipSuccess) break;
-        if ((e = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, h0, hg, cs)) != hipSuccess) break;
-        if ((e = hipEventRecord(done[g], cs)) != hipSuccess) break;
-        if ((e = hipStreamWaitEvent(ds, done[g], 0)) != hipSuccess) break;
-        if (sink) {
-            // hand-off of this group's result: its slice of out goes to the same slice of sink
-            for (int b = 0; b < B && e == hipSuccess; ++b) {
-                const int64_t off = ((int64_t)b * H + h0) * Sq * d;
-                e = pda::launch_copy_f32(out + off, sink + off, (int64_t)hg * Sq * d, ds);
-            }
-            if (e != hipSuccess) break;
-        }
+        if (group_sizes[g] < 1) return fail(PDA_ERR_INVALID_ARG, "group_sizes[%d]=%d (need >= 1)", g, group_sizes[g]);
+        sum += group_sizes[g];
     }
-    if (e == hipSuccess && timed) e = hipEventRecord(drain_end, ds);
-    if (e != hipSuccess) {
-        (void)hipStreamSynchronize(cs);
-        (void)hipStreamSynchronize(ds);
-        cleanup();
-        return hip_fail(e, "head-chunk pipeline");
+    if (sum != H) return fail(PDA_ERR_INVALID_ARG, "group sizes sum to %lld, H=%d", (long long)sum, H);
+    if (sink_layout != PDA_SINK_HEAD_MAJOR && sink_layout != PDA_SINK_TOKEN_ARRIVAL && sink_layout != PDA_SINK_TOKEN_FINAL)
+        return fail(PDA_ERR_INVALID_ARG, "unknown sink_layout=%d", sink_layout);
+    if (sp_ranks < 1) return fail(PDA_ERR_INVALID_ARG, "sp_ranks=%d (need >= 1)", sp_ranks);
+    if (sink_layout != PDA_SINK_HEAD_MAJOR) {
+        if (!sink) return fail(PDA_ERR_INVALID_ARG, "a token-major hand-off needs a sink");
+        if (H % sp_ranks != 0) return fail(PDA_ERR_INVALID_ARG, "H=%d is not a multiple of sp_ranks=%d", H, sp_ranks);
     }
-    if (timed) {
-        if ((e = hipStreamSynchronize(cs)) == hipSuccess) e = hipStreamSynchronize(ds);
-        float ms = 0.f;
-        for (int g = 0; g < n_groups && e == hipSuccess; ++g) {
-            e = hipEventElapsedTime(&ms, beg[g], done[g]);
-            if (group_ms) group_ms[g] = ms;
-        }
-        if (e == hipSuccess && total_ms) {
-            e = hipEventElapsedTime(&ms, beg[0], drain_end);
-            *total_ms = ms;
-        }
-        cleanup();
-        if (e != hipSuccess) return hip_fail(e, "head-chunk timing");
-        return PDA_OK;
+    return run_pipeline(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len,
+                        std::vector<int>(group_sizes, group_sizes + n_groups), sp_ranks, sink_layout,
+                        compute_stream, drain_stream, sink, group_ms, total_ms);
+}
+
+int pda_pipesp_postprocess(const float* const* chunks, int h, int n, int64_t chunk_row_stride,
+                           float* hidden, int64_t rows, int D, void* stream) {
+    if (h < 1 || n < 1) return fail(PDA_ERR_INVALID_ARG, "h=%d n=%d (need >= 1)", h, n);
+    if (h > PDA_MAX_LOCAL_HEADS) return fail(PDA_ERR_UNSUPPORTED, "h=%d exceeds PDA_MAX_LOCAL_HEADS=%d", h, PDA_MAX_LOCAL_HEADS);
+    if (rows < 0) return fail(PDA_ERR_INVALID_ARG, "rows=%lld is negative", (long long)rows);
+    if (D < 4 || D % 4 != 0) return fail(PDA_ERR_UNSUPPORTED, "D=%d (need a positive multiple of 4)", D);
+    if ((double)n * D >= 2147483648.0 || (double)n * D * h >= 2147483648.0) return fail(PDA_ERR_UNSUPPORTED, "n*h*D beyond 2^31");
+    if (chunk_row_stride < (int64_t)n * D || chunk_row_stride % 4 != 0)
+        return fail(PDA_ERR_INVALID_ARG, "chunk_row_stride=%lld (need a multiple of 4, >= n*D=%lld)", (long long)chunk_row_stride, (long long)n * D);
+    if ((double)rows * n * h * D >= 1099511627776.0 || (double)rows * (double)chunk_row_stride >= 1099511627776.0)
+        return fail(PDA_ERR_UNSUPPORTED, "tensor beyond 2^40 elements");
+    if (!chunks) return fail(PDA_ERR_INVALID_ARG, "null chunk array");
+    if (rows == 0) return PDA_OK;
+    if (!hidden) return fail(PDA_ERR_INVALID_ARG, "null hidden");
+    if (!aligned16(hidden)) return fail(PDA_ERR_UNSUPPORTED, "hidden must be 16-byte aligned");
+    pda::PostParams p{};
+    const char* hid0 = reinterpret_cast<const char*>(hidden);
+    const char* hid1 = hid0 + (size_t)rows * n * h * D * sizeof(float);
+    for (int j = 0; j < h; ++j) {
+        if (!chunks[j]) return fail(PDA_ERR_INVALID_ARG, "null chunk %d", j);
+        if (!aligned16(chunks[j])) return fail(PDA_ERR_UNSUPPORTED, "chunk %d must be 16-byte aligned", j);
+        const char* c0 = reinterpret_cast<const char*>(chunks[j]);
+        const char* c1 = c0 + ((size_t)(rows - 1) * chunk_row_stride + (size_t)n * D) * sizeof(float);
+        if (c0 < hid1 && hid0 < c1) return fail(PDA_ERR_INVALID_ARG, "hidden overlaps chunk %d", j);
+        p.chunk[j] = chunks[j];
     }
-    // Untimed: destroying a recorded event is allowed; its resources are released once it completes.
-    cleanup();
+    p.hidden = hidden;
+    p.rows = rows;
+    p.row_stride4 = chunk_row_stride / 4;
+    p.h = h; p.n = n; p.D4 = D / 4;
+    hipError_t e = pda::launch_postprocess(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "post-processing launch");
+    return PDA_OK;
+}
+
+int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, void* stream) {
+    if (B < 0 || H < 0 || S < 0) return fail(PDA_ERR_INVALID_ARG, "negative size (B=%d H=%d S=%lld)", B, H, (long long)S);
+    if (d != 64 && d != 128) return fail(PDA_ERR_UNSUPPORTED, "head dim d=%d not supported (64 or 128)", d);
+    if ((double)B * H * (double)S * d >= 1099511627776.0) return fail(PDA_ERR_UNSUPPORTED, "B*H*S*d overflows 2^40 elements");
+    if (B == 0 || H == 0 || S == 0) return PDA_OK;
+    if (!x || !y) return fail(PDA_ERR_INVALID_ARG, "null x/y");
+    if (!aligned16(x) || !aligned16(y)) return fail(PDA_ERR_UNSUPPORTED, "x and y must be 16-byte aligned");
+    if (static_cast<const void*>(x) == y) return fail(PDA_ERR_INVALID_ARG, "y must not alias x");
+    hipError_t e = pda::launch_pack(x, y, B, S, H, d, unit_rms, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "pack launch");
+    return PDA_OK;
+}
+
+int pda_plan_n_decode(double t_denoise, double t_decode, int N, int* n_decode) {
+    if (!n_decode) return fail(PDA_ERR_INVALID_ARG, "null n_decode");
+    if (N < 2) return fail(PDA_ERR_INVALID_ARG, "N=%d (need >= 2: one GPU per group)", N);
+    if (!(t_denoise > 0.0) || !(t_decode > 0.0) || !std::isfinite(t_denoise) || !std::isfinite(t_decode))
+        return fail(PDA_ERR_INVALID_ARG, "times must be positive and finite");
+    const double raw = std::ceil(t_decode / (t_decode + t_denoise) * N);
+    int v = (int)raw;
+    if (v < 1) v = 1;
+    if (v > N - 1) v = N - 1;
+    *n_decode = v;
+    return PDA_OK;
+}
+
+int pda_plan_aco(double t_L, double t_A, int n_denoise, int n_decode,
+                 double* t_baseline, double* t_coop, double* speedup) {
+    if (n_denoise < 1 || n_decode < 0) return fail(PDA_ERR_INVALID_ARG, "n_denoise=%d n_decode=%d", n_denoise, n_decode);
+    if (!(t_L >= 0.0) || !(t_A >= 0.0) || !std::isfinite(t_L) || !std::isfinite(t_A) || !(t_L + t_A > 0.0))
+        return fail(PDA_ERR_INVALID_ARG, "times must be finite, >= 0 and not both zero");
+    const double base = t_L + t_A;
+    const double coop = t_L + t_A * ((double)n_denoise / (double)(n_denoise + n_decode));
+    if (t_baseline) *t_baseline = base;
+    if (t_coop) *t_coop = coop;
+    if (speedup) *speedup = base / coop;
+    return PDA_OK;
+}
+
+int pda_plan_head_padding(int H, int n_denoise, int* padded_heads, int* heads_per_gpu, int* gpus_needed) {
+    if (H < 1 || n_denoise < 1) return fail(PDA_ERR_INVALID_ARG, "H=%d n_denoise=%d (need >= 1)", H, n_denoise);
+    const int per = (H + n_denoise - 1) / n_denoise;
+    if (padded_heads) *padded_heads = per * n_denoise;
+    if (heads_per_gpu) *heads_per_gpu = per;
+    if (gpus_needed) *gpus_needed = (H + per - 1) / per;
+    return PDA_OK;
+}
+
+int pda_plan_ragged_groups(int H, int n, int* group_sizes) {
+    if (H < 0 || n < 1) return fail(PDA_ERR_INVALID_ARG, "H=%d n=%d", H, n);
+    if (!group_sizes) return fail(PDA_ERR_INVALID_ARG, "null group_sizes");
+    for (int i = 0; i < n; ++i) group_sizes[i] = H / n + (i < H % n ? 1 : 0);
     return PDA_OK;
 }
 

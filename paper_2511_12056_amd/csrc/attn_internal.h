@@ -59,4 +59,22 @@ hipError_t launch_merge(const MergeParams& p, int d, hipStream_t st);
 // Copy n floats (n % 4 == 0, 16-byte aligned) on a stream: the hand-off op of the head-chunk pipeline.
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t st);
 
+// Algorithm 1 steps 10-13 in one pass: hidden[r, i*h + j, :] = chunk[j][r, i, :].
+struct PostParams {
+    const float* chunk[64];  // h device pointers
+    float* hidden;           // [rows, n*h, D]
+    int64_t rows;
+    int64_t row_stride4;     // distance between rows of a chunk, in float4s
+    int h, n, D4;            // D4 = D / 4
+};
+hipError_t launch_postprocess(const PostParams& p, hipStream_t st);
+
+// Hand-off of hg heads [hg, S, d] (global heads h0.. of H = n*h) into a token-major [S, H, d]
+// buffer; arrival != 0 places head i*h+j at slot j*n+i (PipeSP's arrival order), else at i*h+j.
+hipError_t launch_scatter_heads(const float* src, float* dst, int64_t S, int d, int hg, int H, int h0,
+                                int h, int n, int arrival, hipStream_t st);
+
+// Token-major fp32 [B,S,H,d] -> head-major bf16 [B,H,S,d] (d = 64 or 128), optional unit-RMS vectors.
+hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, hipStream_t st);
+
 }  // namespace pda

@@ -23,7 +23,9 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
-    assert names == ["pda_attn_fwd", "pda_attn_merge", "pda_headchunk_run", "pda_last_error", "pda_version"]
+    assert names == ["pda_attn_fwd", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
+                     "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
+                     "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_version"]
     lib = C.CDLL(pda.lib_path())
     for n in names:
         assert getattr(lib, n) is not None
@@ -84,3 +86,64 @@ def test_headchunk_rejects_bad_arguments(pda):
     tot = C.c_float(1.0)
     assert f(None, None, None, None, None, 1, 4, 0, 8, 64, 1.0, 8, 2, 16, 32, None, gms, C.byref(tot)) == 0
     assert list(gms) == [0.0, 0.0] and tot.value == 0.0
+
+
+def test_headchunk_ex_rejects_bad_arguments(pda):
+    f = pda.lib.pda_headchunk_run_ex
+    args = [16, 16, 16, 16, 16, 1, 4, 8, 8, 64, 1.0, 8]
+    g22 = (C.c_int * 2)(2, 2)
+    g21 = (C.c_int * 2)(2, 1)
+    g40 = (C.c_int * 2)(4, 0)
+    assert f(*args, g21, 2, 1, 0, 16, 32, None, None, None) == 1 and "sum" in pda.last_error()
+    assert f(*args, g40, 2, 1, 0, 16, 32, None, None, None) == 1 and "group_sizes[1]" in pda.last_error()
+    assert f(*args, None, 2, 1, 0, 16, 32, None, None, None) == 1
+    assert f(*args, g22, 2, 1, 7, 16, 32, None, None, None) == 1 and "sink_layout" in pda.last_error()
+    assert f(*args, g22, 2, 0, 0, 16, 32, None, None, None) == 1 and "sp_ranks" in pda.last_error()
+    assert f(*args, g22, 2, 2, 1, 16, 32, None, None, None) == 1 and "needs a sink" in pda.last_error()
+    assert f(*args, g22, 2, 3, 2, 16, 32, 64, None, None) == 1 and "multiple" in pda.last_error()
+    assert f(*args, g22, 2, 2, 2, 16, 16, 64, None, None) == 1 and "streams" in pda.last_error()
+
+
+def test_postprocess_rejects_bad_arguments(pda):
+    f = pda.lib.pda_pipesp_postprocess
+    arr = (C.c_void_p * 3)(1 << 20, 2 << 20, 3 << 20)
+    hid = 16 << 20
+    assert f(arr, 0, 2, 256, hid, 4, 128, None) == 1
+    assert f(arr, 3, 0, 256, hid, 4, 128, None) == 1
+    assert f(arr, 65, 2, 256, hid, 4, 128, None) == 2 and "PDA_MAX_LOCAL_HEADS" in pda.last_error()
+    assert f(arr, 3, 2, 256, hid, -1, 128, None) == 1
+    assert f(arr, 3, 2, 256, hid, 4, 126, None) == 2
+    assert f(arr, 3, 2, 255, hid, 4, 128, None) == 1 and "chunk_row_stride" in pda.last_error()
+    assert f(arr, 3, 2, 254, hid, 4, 128, None) == 1
+    assert f(None, 3, 2, 256, hid, 4, 128, None) == 1
+    assert f(arr, 3, 2, 256, None, 4, 128, None) == 1
+    assert f(arr, 3, 2, 256, hid + 4, 4, 128, None) == 2
+    bad = (C.c_void_p * 3)(1 << 20, None, 3 << 20)
+    assert f(bad, 3, 2, 256, hid, 4, 128, None) == 1
+    assert f(arr, 3, 2, 256, (2 << 20) + 1024, 4, 128, None) == 1 and "overlaps" in pda.last_error()
+    assert f(arr, 3, 2, 256, hid, 0, 128, None) == 0
+
+
+def test_pack_rejects_bad_arguments(pda):
+    f = pda.lib.pda_pack_heads
+    assert f(64, 128, 1, 8, 2, 32, 1, None) == 2 and "head dim" in pda.last_error()
+    assert f(64, 128, -1, 8, 2, 64, 1, None) == 1
+    assert f(None, 128, 1, 8, 2, 64, 1, None) == 1
+    assert f(64, 72, 1, 8, 2, 64, 1, None) == 2
+    assert f(64, 64, 1, 8, 2, 64, 1, None) == 1 and "alias" in pda.last_error()
+    assert f(None, None, 1, 0, 2, 64, 1, None) == 0
+
+
+def test_planner_rejects_bad_arguments(pda):
+    out = C.c_int(0)
+    assert pda.lib.pda_plan_n_decode(1.0, 1.0, 1, C.byref(out)) == 1
+    assert pda.lib.pda_plan_n_decode(0.0, 1.0, 8, C.byref(out)) == 1
+    assert pda.lib.pda_plan_n_decode(1.0, float("inf"), 8, C.byref(out)) == 1
+    assert pda.lib.pda_plan_n_decode(1.0, 1.0, 8, None) == 1
+    assert pda.lib.pda_plan_aco(0.0, 0.0, 4, 4, None, None, None) == 1
+    assert pda.lib.pda_plan_aco(1.0, 1.0, 0, 4, None, None, None) == 1
+    assert pda.lib.pda_plan_aco(1.0, -1.0, 4, 4, None, None, None) == 1
+    assert pda.lib.pda_plan_aco(1.0, 1.0, 4, 4, None, None, None) == 0
+    assert pda.lib.pda_plan_head_padding(0, 4, None, None, None) == 1
+    assert pda.lib.pda_plan_ragged_groups(4, 0, C.byref(out)) == 1
+    assert pda.lib.pda_plan_ragged_groups(4, 2, None) == 1
