@@ -60,12 +60,87 @@ def cpu_baseline(w, qb, kb, vb, target_s=15.0):
             "full_problem_extrapolated_s": w.flops / (flops / dt)}
 
 
+def _event_ms(torch, stream, fn, iters=5):
+    """Mean duration of fn() (which enqueues on `stream`) over `iters` calls, by events on that stream."""
+    fn()
+    stream.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(iters):
+        fn()
+    b.record(stream)
+    stream.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, t_linear_ms):
+    """The steps next to the attention call at the same 720p shape, outside the timed step:
+    post-processing, token-major hand-off, pack, unequal vs padded head groups, planner."""
+    S, H, d, hg = w.Sq, w.H, w.d, w.heads_per_group
+    n = H // hg                                              # 8 simulated GPUs with 3 local heads each
+    res = {}
+
+    def bw(name, ms, nbytes, extra=None):
+        gbs = nbytes / (ms * 1e-3) * 1e-9
+        res[name] = {"bound": "hbm", "launch_ms": ms, "bytes_per_launch": nbytes, "achieved": gbs, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+        if extra:
+            res[name].update(extra)
+
+    # Algorithm 1 steps 10-13 over every receiver's rows at once: [S, 24, 128] fp32 in and out
+    t_mod, hidden = sink.view(S, H, d), out.view(S, H, d)
+    ms = _event_ms(torch, cs, lambda: pda.pipesp_postprocess(t_mod, hg, n, hidden, stream=cs))
+    bw("pipesp_postprocess", ms, 2.0 * S * H * d * 4, {"kernel": "postprocess_kernel", "rows": S, "h": hg, "n": n})
+
+    # pack: token-major fp32 [1,S,24,128] -> head-major bf16, unit-RMS vectors
+    x = out.view(1, S, H, d)
+    y = torch.empty(1, H, S, d, dtype=torch.bfloat16, device="cuda")
+    ms = _event_ms(torch, cs, lambda: pda.pack_heads(x, y, True, stream=cs))
+    bw("pack_heads_unit_rms", ms, S * H * d * 6.0, {"kernel": "pack_heads_kernel<32>"})
+    del y
+
+    # head-chunk pipeline with the post-processing folded into the hand-off (token-major, final order)
+    tok = sink.view(1, S, H, d)
+    pda.headchunk_run_ex(q, k, v, out, lse, w.scale, [hg] * n, cs, ds, sink=tok, sp_ranks=n,
+                         sink_layout=pda.PDA_SINK_TOKEN_FINAL, timed=True)
+    gms, tms = pda.headchunk_run_ex(q, k, v, out, lse, w.scale, [hg] * n, cs, ds, sink=tok, sp_ranks=n,
+                                    sink_layout=pda.PDA_SINK_TOKEN_FINAL, timed=True)
+    res["headchunk_token_major_final"] = {"total_ms": tms, "sum_group_ms": sum(gms)}
+
+    # 24 heads on 7 GPUs played one after the other: padded to 28 heads (7 groups of 4) against the
+    # unequal split 4,4,4,3,3,3,3.  The padding heads repeat real heads so that they cost the same.
+    n7 = 7
+    padded, per, needed = pda.plan_head_padding(H, n7)
+    pad = padded - H
+    qp, kp, vp = (torch.cat([t, t[:, :pad]], dim=1) for t in (q, k, v))
+    outp = torch.empty(1, padded, S, d, device="cuda")
+    lsep = torch.empty(1, padded, S, device="cuda")
+    gp, tp = pda.headchunk_run_ex(qp, kp, vp, outp, lsep, w.scale, [per] * n7, cs, ds, timed=True)
+    del qp, kp, vp, outp, lsep
+    groups = pda.plan_ragged_groups(H, n7)
+    gr, tr = pda.headchunk_run_ex(q, k, v, out, lse, w.scale, groups, cs, ds, timed=True)
+    res["heads_24_on_7_gpus"] = {"padded_heads": padded, "heads_per_gpu": per, "gpus_needed": needed,
+                                 "padded_group_ms": gp, "padded_total_ms": tp, "ragged_groups": groups,
+                                 "ragged_group_ms": gr, "ragged_total_ms": tr,
+                                 "gpu_time_wasted_by_padding": 1.0 - tr / tp,
+                                 "critical_path_ms": {"padded": max(gp), "ragged": max(gr)}}
+
+    # planner fed with the measured attention time of one GPU's share (t_A) and a supplied t_L
+    t_A = sum(gms) / n
+    t_L = t_linear_ms if t_linear_ms is not None else 0.25 * t_A
+    res["planner"] = {"t_A_ms": t_A, "t_L_ms": t_L, "t_L_source": "argument" if t_linear_ms is not None else "assumed 0.25 * t_A",
+                      "aco": {f"{a}+{b}": pda.plan_aco(t_L, t_A, a, b)[2] for a, b in ((7, 1), (6, 2), (4, 4))}}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true", help="skip the measurements of the steps next to the attention call")
+    ap.add_argument("--t-linear-ms", type=float, default=None, help="time of the linear projections for the planner example")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -157,6 +232,9 @@ def main():
                      "sum_group_ms_mean": sum(group_ms_all) / args.steps, "split_pass_ms": split_ms,
                      "chunked_tflops": flops_chunked / (sum(total_ms_all) / len(total_ms_all) * 1e-3) * 1e-12},
     }
+    if not args.no_next_rows:
+        del qr, qr_out, kc, kc_out
+        res["next_rows"] = next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, args.t_linear_ms)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, qb, kb, vb)
     print(json.dumps(res))
