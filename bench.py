@@ -80,23 +80,24 @@ def next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, t_linear_ms):
     n = H // hg                                              # 8 simulated GPUs with 3 local heads each
     res = {}
 
-    def bw(name, ms, nbytes, extra=None):
+    def bw(name, ms, nbytes, extra=None, traffic_key=None):
         gbs = nbytes / (ms * 1e-3) * 1e-9
         res[name] = {"bound": "hbm", "launch_ms": ms, "bytes_per_launch": nbytes, "achieved": gbs, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic(traffic_key)}
         if extra:
             res[name].update(extra)
 
     # Algorithm 1 steps 10-13 over every receiver's rows at once: [S, 24, 128] fp32 in and out
     t_mod, hidden = sink.view(S, H, d), out.view(S, H, d)
     ms = _event_ms(torch, cs, lambda: pda.pipesp_postprocess(t_mod, hg, n, hidden, stream=cs))
-    bw("pipesp_postprocess", ms, 2.0 * S * H * d * 4, {"kernel": "postprocess_kernel", "rows": S, "h": hg, "n": n})
+    bw("pipesp_postprocess", ms, 2.0 * S * H * d * 4, {"kernel": "postprocess_kernel", "rows": S, "h": hg, "n": n},
+       "postprocess_kernel")
 
     # pack: token-major fp32 [1,S,24,128] -> head-major bf16, unit-RMS vectors
     x = out.view(1, S, H, d)
     y = torch.empty(1, H, S, d, dtype=torch.bfloat16, device="cuda")
     ms = _event_ms(torch, cs, lambda: pda.pack_heads(x, y, True, stream=cs))
-    bw("pack_heads_unit_rms", ms, S * H * d * 6.0, {"kernel": "pack_heads_kernel<32>"})
+    bw("pack_heads_unit_rms", ms, S * H * d * 6.0, {"kernel": "pack_heads_kernel<32>"}, "pack_heads_kernel_32")
     del y
 
     # head-chunk pipeline with the post-processing folded into the hand-off (token-major, final order)
