@@ -233,6 +233,11 @@ def main():
                      "sum_group_ms_mean": sum(group_ms_all) / args.steps, "split_pass_ms": split_ms,
                      "chunked_tflops": flops_chunked / (sum(total_ms_all) / len(total_ms_all) * 1e-3) * 1e-12},
     }
+    # context for the clock the chip sustains on this data: an MFMA-only loop fed with Q's values
+    probe_tf, probe_ms = pda.probe_mfma_rate(q, 1 << 20, stream=cs)
+    res["roofline"]["mfma_only_same_data"] = {"achieved": probe_tf, "unit": "TFLOP/s", "ms": probe_ms,
+                                              "what": "loop of bf16 32x32x16 MFMAs only, operands = values of Q, 2 wavefronts per SIMD"}
+    res["roofline"]["frac_of_mfma_only"] = achieved / probe_tf
     if not args.no_next_rows:
         del qr, qr_out, kc, kc_out
         res["next_rows"] = next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, args.t_linear_ms)

@@ -206,6 +206,20 @@ int pda_plan_aco(double t_L, double t_A, int n_denoise, int n_decode,
 int pda_plan_head_padding(int H, int n_denoise, int* padded_heads, int* heads_per_gpu, int* gpus_needed);
 int pda_plan_ragged_groups(int H, int n, int* group_sizes);
 
+/*
+ * Measurement aid for the roofline: the rate the matrix cores alone sustain on this device on
+ * the caller's data.  Runs a loop of nothing but bf16 MFMAs (32x32x16, fp32 accumulate, the
+ * instruction the attention kernel uses) whose operand fragments are read once from
+ * operands (device, bf16, n_elems >= 4096 elements, 16-byte aligned; e.g. the Q tensor of the
+ * workload), on every compute unit with two wavefronts per SIMD, for mfma_per_wave MFMAs per
+ * wavefront (rounded up to a multiple of 8; about 1e6 gives a 30 ms run), timed with events on
+ * the stream.  SYNCHRONOUS.  tflops (HOST pointer) receives the measured rate in TFLOP/s,
+ * ms (HOST, optional) the duration.  The sustained clock, and with it this rate, depends on the
+ * operand values (constant operands run faster than random ones).
+ */
+int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave,
+                        float* tflops, float* ms, void* stream);
+
 /* Message of the calling thread's most recent failure ("" if none). Never NULL. */
 const char* pda_last_error(void);
 

@@ -58,6 +58,8 @@ def _load() -> C.CDLL:
     lib.pda_plan_head_padding.restype = i32
     lib.pda_plan_ragged_groups.argtypes = [i32, i32, C.POINTER(i32)]
     lib.pda_plan_ragged_groups.restype = i32
+    lib.pda_probe_mfma_rate.argtypes = [vp, i64, i64, C.POINTER(f32), C.POINTER(f32), vp]
+    lib.pda_probe_mfma_rate.restype = i32
     lib.pda_last_error.argtypes = []
     lib.pda_last_error.restype = C.c_char_p
     lib.pda_version.argtypes = []
@@ -252,3 +254,14 @@ def plan_ragged_groups(H: int, n: int):
     arr = (C.c_int * max(int(n), 1))()
     _check(lib.pda_plan_ragged_groups(int(H), int(n), arr))
     return [arr[i] for i in range(int(n))]
+
+
+def probe_mfma_rate(operands, mfma_per_wave: int = 1 << 20, stream=None):
+    """pda_probe_mfma_rate on a bf16 tensor: (TFLOP/s, ms) of an MFMA-only loop fed with its values."""
+    import torch
+    if operands.dtype != torch.bfloat16 or not operands.is_contiguous() or not operands.is_cuda:
+        raise ValueError("operands: expected a contiguous cuda bf16 tensor")
+    tf, ms = C.c_float(0.0), C.c_float(0.0)
+    _check(lib.pda_probe_mfma_rate(_ptr(operands), operands.numel(), int(mfma_per_wave), C.byref(tf), C.byref(ms),
+                                   _stream_handle(stream)))
+    return tf.value, ms.value

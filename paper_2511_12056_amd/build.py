@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipedit_attn.so")
-SOURCES = ["attn_fwd.hip", "attn_fwd_sp.hip", "merge.hip", "layout.hip", "api.hip"]
+SOURCES = ["attn_fwd.hip", "attn_fwd_sp.hip", "merge.hip", "layout.hip", "probe.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -333,6 +333,37 @@ int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int 
     return PDA_OK;
 }
 
+int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave,
+                        float* tflops, float* ms, void* stream) {
+    if (!operands || !tflops) return fail(PDA_ERR_INVALID_ARG, "null operands/tflops");
+    if (n_elems < 4096) return fail(PDA_ERR_INVALID_ARG, "n_elems=%lld (need >= 4096)", (long long)n_elems);
+    if (mfma_per_wave < 1 || mfma_per_wave > ((int64_t)1 << 32)) return fail(PDA_ERR_INVALID_ARG, "mfma_per_wave out of range");
+    if (!aligned16(operands)) return fail(PDA_ERR_UNSUPPORTED, "operands must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int dev = 0, n_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    float* sink = nullptr;
+    if (e == hipSuccess) e = pda::attn_workspace(st, 512 * sizeof(float), &sink);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    const int64_t iters = (mfma_per_wave + 7) / 8;
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventRecord(e0, st);
+    if (e == hipSuccess) e = pda::launch_mfma_rate(operands, n_elems / 8, iters, n_cu, sink, st);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(e, "MFMA rate probe");
+    const double flop = (double)n_cu * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+    *tflops = (float)(flop / ((double)t * 1e-3) * 1e-12);
+    if (ms) *ms = t;
+    return PDA_OK;
+}
+
 int pda_plan_n_decode(double t_denoise, double t_decode, int N, int* n_decode) {
     if (!n_decode) return fail(PDA_ERR_INVALID_ARG, "null n_decode");
     if (N < 2) return fail(PDA_ERR_INVALID_ARG, "N=%d (need >= 2: one GPU per group)", N);

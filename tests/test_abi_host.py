@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
     assert names == ["pda_attn_fwd", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
-                     "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_version"]
+                     "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_mfma_rate", "pda_version"]
     lib = C.CDLL(pda.lib_path())
     for n in names:
         assert getattr(lib, n) is not None
@@ -147,3 +147,13 @@ def test_planner_rejects_bad_arguments(pda):
     assert pda.lib.pda_plan_head_padding(0, 4, None, None, None) == 1
     assert pda.lib.pda_plan_ragged_groups(4, 0, C.byref(out)) == 1
     assert pda.lib.pda_plan_ragged_groups(4, 2, None) == 1
+
+
+def test_probe_rejects_bad_arguments(pda):
+    f = pda.lib.pda_probe_mfma_rate
+    out = C.c_float(0)
+    assert f(None, 8192, 1000, C.byref(out), None, None) == 1
+    assert f(64, 100, 1000, C.byref(out), None, None) == 1
+    assert f(64, 8192, 0, C.byref(out), None, None) == 1
+    assert f(64, 8192, 1000, None, None, None) == 1
+    assert f(72, 8192, 1000, C.byref(out), None, None) == 2

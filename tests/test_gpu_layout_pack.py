@@ -188,3 +188,13 @@ def test_pack_feeds_attention():
     for hh in range(H):
         ro, rl = attention_head(qo[0, hh], ko[0, hh], vo[0, hh], d ** -0.5, S)
         assert_close(out[0, hh].cpu().numpy(), lse[0, hh].cpu().numpy(), ro, rl, f"pack+attention head {hh}")
+
+
+def test_mfma_rate_probe_runs():
+    import torch
+    import paper_2511_12056_amd as pda
+    x = torch.randn(1 << 16, device="cuda").to(torch.bfloat16)
+    tf, ms = pda.probe_mfma_rate(x, 1 << 14)
+    assert ms > 0 and 100.0 < tf < 2600.0, (tf, ms)          # between a tenth of and the nominal bf16 peak
+    tz, _ = pda.probe_mfma_rate(torch.zeros_like(x), 1 << 14)
+    assert 100.0 < tz < 2600.0
