@@ -4,7 +4,8 @@ One step = one pass of the whole path over one batch of synthetic Q/K/V resident
   1. pda_headchunk_run: 24 heads x 119 056 tokens x d=128 as 8 groups of 3 heads, two streams,
      hand-off copy of every group's result (the PipeSP loop on one GPU's heads);
   2. the Aco-style work split on the first 6 heads: three query ranges (40/35/25 %) as separate
-     pda_attn_fwd calls, then four key chunks as separate calls merged by pda_attn_merge.
+     pda_attn_fwd_strided calls on views, then four key chunks as separate calls merged by
+     pda_attn_merge.
 Prints ONE JSON line (see README for the fields).
 """
 from __future__ import annotations
@@ -160,14 +161,16 @@ def main():
     sink = torch.empty_like(out)
     cs, ds = torch.cuda.Stream(), torch.cuda.Stream()
 
-    # Aco-style split on the first 6 heads (views of the same tensors; B == 1 so head slices are compact)
+    # Aco-style split on the first 6 heads: query ranges and key chunks are VIEWS of the same
+    # tensors (pda_attn_fwd_strided, no copies); query ranges write their rows of one full result
     H5 = w5.H
     q5, k5, v5 = q[:, :H5], k[:, :H5], v[:, :H5]
     out5 = torch.empty(1, H5, w.Sq, w.d, device="cuda")
     lse5 = torch.empty(1, H5, w.Sq, device="cuda")
-    qr = [(q5[:, :, o:o + n].contiguous(), o, n) for o, n in w5.query_ranges]
-    qr_out = [(torch.empty(1, H5, n, w.d, device="cuda"), torch.empty(1, H5, n, device="cuda")) for _, _, n in qr]
-    kc = [(k5[:, :, o:o + n].contiguous(), v5[:, :, o:o + n].contiguous()) for o, n in w5.key_chunks]
+    outq = torch.empty(1, H5, w.Sq, w.d, device="cuda")
+    lseq = torch.empty(1, H5, w.Sq, device="cuda")
+    qr = [(q5[:, :, o:o + n], o, outq[:, :, o:o + n], lseq[:, :, o:o + n]) for o, n in w5.query_ranges]
+    kc = [(k5[:, :, o:o + n], v5[:, :, o:o + n]) for o, n in w5.key_chunks]
     kc_out = [(torch.empty_like(out5), torch.empty_like(lse5)) for _ in kc]
     merge_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     split_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -180,10 +183,10 @@ def main():
             group_ms_all.extend(gms); total_ms_all.append(tms)
         with torch.cuda.stream(cs):
             if timed: split_ev[i][0].record(cs)
-            for (qq, off, n), (oo, ll) in zip(qr, qr_out):
-                pda.attn_fwd(qq, k5, v5, oo, ll, w.scale, None, off, stream=cs)
+            for qq, off, oo, ll in qr:
+                pda.attn_fwd_strided(qq, k5, v5, oo, ll, w.scale, None, off, stream=cs)
             for (kk, vv), (oo, ll) in zip(kc, kc_out):
-                pda.attn_fwd(q5, kk, vv, oo, ll, w.scale, None, 0, stream=cs)
+                pda.attn_fwd_strided(q5, kk, vv, oo, ll, w.scale, None, 0, stream=cs)
             if timed: split_ev[i][1].record(cs); merge_ev[i][0].record(cs)
             pda.attn_merge([o for o, _ in kc_out], [l for _, l in kc_out], out5, lse5, stream=cs)
             if timed: merge_ev[i][1].record(cs)
@@ -239,7 +242,7 @@ def main():
                                               "what": "loop of bf16 32x32x16 MFMAs only, operands = values of Q, 2 wavefronts per SIMD"}
     res["roofline"]["frac_of_mfma_only"] = achieved / probe_tf
     if not args.no_next_rows:
-        del qr, qr_out, kc, kc_out
+        del qr, kc, kc_out, outq, lseq
         res["next_rows"] = next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, args.t_linear_ms)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, qb, kb, vb)

@@ -72,6 +72,25 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
                  int64_t kv_valid_len, int64_t q_offset, void* stream);
 
 /*
+ * pda_attn_fwd on views: the same computation with explicit batch and head strides (in
+ * ELEMENTS) for q, k/v (shared), out and lse, so that a query range or a key chunk of larger
+ * tensors is passed without a copy (Attention Co-processing shares; Ring-Attention style key
+ * chunks): q = Q + q_offset*d with Q's strides, k = K + chunk_start*d with K's strides, and so on.
+ * Rows stay compact (consecutive rows are d elements apart).  Strides of q and k/v must be
+ * multiples of 8, of out multiples of 4 (16-byte alignment of every row); the head stride of out
+ * must be >= Sq*d and of lse >= Sq, and with B > 1 a batch must not overlap the next one
+ * (batch stride >= (H-1)*head stride + extent of one head), for out and lse, which are written.
+ * pda_attn_fwd is this call with the strides of compact [B,H,S,d] tensors.
+ */
+int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d,
+                         int64_t q_batch_stride, int64_t q_head_stride,
+                         int64_t kv_batch_stride, int64_t kv_head_stride,
+                         int64_t out_batch_stride, int64_t out_head_stride,
+                         int64_t lse_batch_stride, int64_t lse_head_stride,
+                         float scale, int64_t kv_valid_len, int64_t q_offset, void* stream);
+
+/*
  * Exact merge of n partial attentions computed over disjoint key sets (the
  * recombination a Ring-Attention style key split needs, and what re-joins
  * query ranges when each range is embedded in a full-length partial whose

@@ -37,6 +37,8 @@ def _load() -> C.CDLL:
     vp, fp, i32, i64, f32 = C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_float
     lib.pda_attn_fwd.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i64, vp]
     lib.pda_attn_fwd.restype = i32
+    lib.pda_attn_fwd_strided.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32] + [i64] * 8 + [f32, i64, i64, vp]
+    lib.pda_attn_fwd_strided.restype = i32
     lib.pda_attn_merge.argtypes = [C.POINTER(vp), C.POINTER(vp), i32, fp, fp, i64, i32, vp]
     lib.pda_attn_merge.restype = i32
     lib.pda_headchunk_run.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i32, vp, vp, fp,
@@ -115,6 +117,41 @@ def attn_fwd(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None
     n_v = Skv if kv_valid_len is None else int(kv_valid_len)
     _check(lib.pda_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
                             n_v, int(q_offset), _stream_handle(stream)))
+    return out, lse
+
+
+def _view_strides(t, inner, name):
+    """(batch stride, head stride) of a [B,H,S,...] view whose rows are compact."""
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a cuda tensor")
+    st = t.stride()
+    if inner == 2 and (st[3] != 1 or st[2] != t.shape[3]):
+        raise ValueError(f"{name}: rows must be compact (stride {st})")
+    if inner == 1 and st[2] != 1:
+        raise ValueError(f"{name}: rows must be compact (stride {st})")
+    return int(st[0]), int(st[1])
+
+
+def attn_fwd_strided(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None, q_offset: int = 0, stream=None):
+    """pda_attn_fwd_strided: as attn_fwd, on [B,H,S,d] VIEWS (e.g. x[:, :, a:b]) with compact rows; no copies."""
+    import torch
+    B, H, Sq, d = q.shape
+    Skv = k.shape[2]
+    if q.dtype != torch.bfloat16 or k.dtype != torch.bfloat16 or v.dtype != torch.bfloat16:
+        raise ValueError("q/k/v: expected bf16")
+    if out.dtype != torch.float32 or lse.dtype != torch.float32:
+        raise ValueError("out/lse: expected fp32")
+    if tuple(k.shape) != (B, H, Skv, d) or tuple(v.shape) != (B, H, Skv, d) or tuple(out.shape) != (B, H, Sq, d) \
+            or tuple(lse.shape) != (B, H, Sq):
+        raise ValueError("shape mismatch")
+    qs, ks, vs, os_, ls = (_view_strides(q, 2, "q"), _view_strides(k, 2, "k"), _view_strides(v, 2, "v"),
+                           _view_strides(out, 2, "out"), _view_strides(lse, 1, "lse"))
+    if ks != vs:
+        raise ValueError("k and v must share their strides")
+    n_v = Skv if kv_valid_len is None else int(kv_valid_len)
+    _check(lib.pda_attn_fwd_strided(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d,
+                                    qs[0], qs[1], ks[0], ks[1], os_[0], os_[1], ls[0], ls[1],
+                                    float(scale), n_v, int(q_offset), _stream_handle(stream)))
     return out, lse
 
 

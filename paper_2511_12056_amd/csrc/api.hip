@@ -59,27 +59,46 @@ int check_attn_args(const void* q, const void* k, const void* v, const float* ou
     return PDA_OK;
 }
 
-// Launch attention for heads [h0, h0+hg) of compact [B,H,S,d] tensors.
-hipError_t launch_heads(const void* q, const void* k, const void* v, float* out, float* lse,
-                        int B, int H, int64_t Sq, int64_t Skv, int d, float scale, int64_t n_v,
-                        int h0, int hg, hipStream_t st) {
+// Batch and head strides (elements) of the four tensor kinds of an attention call.
+struct Strides {
+    int64_t q_bs, q_hs, kv_bs, kv_hs, o_bs, o_hs, l_bs, l_hs;
+};
+
+Strides compact_strides(int H, int64_t Sq, int64_t Skv, int d) {
+    return {(int64_t)H * Sq * d, Sq * d, (int64_t)H * Skv * d, Skv * d, (int64_t)H * Sq * d, Sq * d, (int64_t)H * Sq, Sq};
+}
+
+// Launch attention for hg heads of B batches; the pointers address the first of those heads.
+hipError_t launch_strided(const void* q, const void* k, const void* v, float* out, float* lse,
+                          int B, int hg, int64_t Sq, int d, const Strides& s, float scale, int64_t n_v, hipStream_t st) {
     pda::AttnParams p{};
-    p.q = static_cast<const __bf16*>(q) + (int64_t)h0 * Sq * d;
-    p.k = static_cast<const __bf16*>(k) + (int64_t)h0 * Skv * d;
-    p.v = static_cast<const __bf16*>(v) + (int64_t)h0 * Skv * d;
-    p.out = out + (int64_t)h0 * Sq * d;
-    p.lse = lse + (int64_t)h0 * Sq;
+    p.q = static_cast<const __bf16*>(q);
+    p.k = static_cast<const __bf16*>(k);
+    p.v = static_cast<const __bf16*>(v);
+    p.out = out;
+    p.lse = lse;
     p.Sq = Sq;
     p.n_v = n_v;
-    p.q_hs = Sq * d;   p.q_bs = (int64_t)H * Sq * d;
-    p.kv_hs = Skv * d; p.kv_bs = (int64_t)H * Skv * d;
-    p.o_hs = Sq * d;   p.o_bs = (int64_t)H * Sq * d;
-    p.l_hs = Sq;       p.l_bs = (int64_t)H * Sq;
+    p.q_hs = s.q_hs;   p.q_bs = s.q_bs;
+    p.kv_hs = s.kv_hs; p.kv_bs = s.kv_bs;
+    p.o_hs = s.o_hs;   p.o_bs = s.o_bs;
+    p.l_hs = s.l_hs;   p.l_bs = s.l_bs;
     p.Hg = hg;
     p.scale = scale;
     // scale 0 is run with a tiny positive factor so that hidden keys (-inf scores) still get exp2(-inf) = 0
     p.scale_log2e = std::fmax(scale * 1.4426950408889634f, 1e-37f);
     return pda::launch_attn_fwd(p, B * hg, d, attn_variant(), st);
+}
+
+// Launch attention for heads [h0, h0+hg) of compact [B,H,S,d] tensors.
+hipError_t launch_heads(const void* q, const void* k, const void* v, float* out, float* lse,
+                        int B, int H, int64_t Sq, int64_t Skv, int d, float scale, int64_t n_v,
+                        int h0, int hg, hipStream_t st) {
+    return launch_strided(static_cast<const __bf16*>(q) + (int64_t)h0 * Sq * d,
+                          static_cast<const __bf16*>(k) + (int64_t)h0 * Skv * d,
+                          static_cast<const __bf16*>(v) + (int64_t)h0 * Skv * d,
+                          out + (int64_t)h0 * Sq * d, lse + (int64_t)h0 * Sq,
+                          B, hg, Sq, d, compact_strides(H, Sq, Skv, d), scale, n_v, st);
 }
 
 // The head-chunk pipeline (Algorithm 1, steps 2-9) over the given groups; arguments already validated.
@@ -211,6 +230,32 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
     hipError_t e = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H,
                                 static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "attention launch");
+    return PDA_OK;
+}
+
+int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d,
+                         int64_t q_batch_stride, int64_t q_head_stride,
+                         int64_t kv_batch_stride, int64_t kv_head_stride,
+                         int64_t out_batch_stride, int64_t out_head_stride,
+                         int64_t lse_batch_stride, int64_t lse_head_stride,
+                         float scale, int64_t kv_valid_len, int64_t q_offset, void* stream) {
+    int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len);
+    if (rc != PDA_OK) return rc;
+    if (q_offset < 0) return fail(PDA_ERR_INVALID_ARG, "q_offset=%lld is negative", (long long)q_offset);
+    const Strides s{q_batch_stride, q_head_stride, kv_batch_stride, kv_head_stride,
+                    out_batch_stride, out_head_stride, lse_batch_stride, lse_head_stride};
+    const int64_t all[8] = {s.q_bs, s.q_hs, s.kv_bs, s.kv_hs, s.o_bs, s.o_hs, s.l_bs, s.l_hs};
+    for (int64_t x : all)
+        if (x < 0 || x >= ((int64_t)1 << 40)) return fail(PDA_ERR_INVALID_ARG, "stride %lld outside [0, 2^40)", (long long)x);
+    if ((s.q_bs | s.q_hs | s.kv_bs | s.kv_hs) % 8 != 0) return fail(PDA_ERR_UNSUPPORTED, "q and k/v strides must be multiples of 8 elements");
+    if ((s.o_bs | s.o_hs) % 4 != 0) return fail(PDA_ERR_UNSUPPORTED, "out strides must be multiples of 4 elements");
+    if (H > 1 && (s.o_hs < Sq * d || s.l_hs < Sq)) return fail(PDA_ERR_INVALID_ARG, "heads of out/lse overlap (head stride too small)");
+    if (B > 1 && (s.o_bs < (int64_t)(H - 1) * s.o_hs + Sq * d || s.l_bs < (int64_t)(H - 1) * s.l_hs + Sq))
+        return fail(PDA_ERR_INVALID_ARG, "batches of out/lse overlap (batch stride too small)");
+    if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
+    hipError_t e = launch_strided(q, k, v, out, lse, B, H, Sq, d, s, scale, kv_valid_len, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "attention launch");
     return PDA_OK;
 }

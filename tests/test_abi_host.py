@@ -23,7 +23,7 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
-    assert names == ["pda_attn_fwd", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
+    assert names == ["pda_attn_fwd", "pda_attn_fwd_strided", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
                      "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_mfma_rate", "pda_version"]
     lib = C.CDLL(pda.lib_path())
@@ -157,3 +157,22 @@ def test_probe_rejects_bad_arguments(pda):
     assert f(64, 8192, 0, C.byref(out), None, None) == 1
     assert f(64, 8192, 1000, None, None, None) == 1
     assert f(72, 8192, 1000, C.byref(out), None, None) == 2
+
+
+def test_attn_fwd_strided_rejects_bad_arguments(pda):
+    f = pda.lib.pda_attn_fwd_strided
+    base = [128, 128, 128, 128, 128, 2, 2, 8, 8, 64]
+    good = [2048, 1024, 2048, 1024, 2048, 1024, 32, 16]
+
+    def call(strides, scale=1.0, n_v=8, qoff=0, shape=None):
+        return f(*(shape or base), *strides, scale, n_v, qoff, None)
+
+    assert call(good, n_v=9) == 1
+    assert call(good, qoff=-1) == 1
+    assert call([2048, 1020] + good[2:]) == 2 and "multiples of 8" in pda.last_error()
+    assert call(good[:4] + [2048, 1022] + good[6:]) == 2 and "multiples of 4" in pda.last_error()
+    assert call(good[:5] + [256] + good[6:]) == 1 and "head stride" in pda.last_error()
+    assert call(good[:7] + [4]) == 1
+    assert call(good[:4] + [1024, 1024] + good[6:]) == 1 and "batch stride" in pda.last_error()
+    assert call([-8] + good[1:]) == 1
+    assert call(good, shape=[128, 128, 128, 128, 128, 2, 2, 0, 8, 64]) == 0      # empty: no-op
