@@ -298,13 +298,9 @@ static hipError_t launch_variant(const AttnParams& p, int BH, hipStream_t st) {
     constexpr int M = 32 * NQ * NW;
     constexpr int smem = 4 * BN * D * 2;
     auto kern = attn_fwd_kernel<D, NQ, NW, BN, MINB>;
-    static bool attr_set = false;       // benign race: setting the attribute twice is harmless
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static KernelSetup setup;
+    hipError_t e = setup.ensure(reinterpret_cast<const void*>(kern), smem, nullptr);
+    if (e != hipSuccess) return e;
     dim3 grid((unsigned)((p.Sq + M - 1) / M), (unsigned)BH);
     hipLaunchKernelGGL(kern, grid, dim3(64 * NW), smem, st, p);
     return hipGetLastError();

@@ -502,26 +502,35 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
     constexpr int M = 256, D = 128;
     auto kern = attn_fwd_sp_kernel<NQ>;
-    static bool attr_set = false;
-    static int n_cu = 0;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static KernelSetup setup;
+    int n_cu = 0;
+    {
+        hipError_t e = setup.ensure(reinterpret_cast<const void*>(kern), smem, &n_cu);
         if (e != hipSuccess) return e;
-        int dev = 0;
-        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-        if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-        attr_set = true;
     }
-    // Work plan: one workgroup per CU at a time, so tiles run in rounds of n_cu.  The tiles of the
-    // last, partly filled round are cut into `split` key ranges (as many as fit in that round, at
-    // most 4, each at least 8 key tiles long).
+    // Work plan: one workgroup per CU at a time, so tiles run in rounds of n_cu and a partly
+    // filled last round wastes the rest of the machine.  The tiles of the last round - and, if
+    // that pays, of the full round before it - are cut into `split` key ranges (at most 4, each at
+    // least 8 key tiles long), so that the tail is made of shorter items.  Cost of a plan in
+    // tile-times: whole rounds + ceil(cut tiles * split / n_cu) / split, plus a small charge per
+    // cut tile for the partial stores and the merge pass.
     p.tiles_per_head = (int)((p.Sq + M - 1) / M);
     const int64_t n_tiles = (int64_t)p.tiles_per_head * BH;
+    const int64_t rounds = n_tiles / n_cu;
     const int rem = (int)(n_tiles % n_cu);
-    int split = rem ? n_cu / rem : 1;
-    if (split > 4) split = 4;
-    while (split > 1 && p.n_v < (int64_t)split * 8 * 64) --split;
+    int split = 1;
+    int64_t n_cut = 0;
+    if (rem) {
+        double best = (double)rounds + 1.0;
+        for (int extra = 0; extra <= (rounds > 0 ? 1 : 0); ++extra) {
+            const int64_t cut = rem + (int64_t)extra * n_cu;
+            for (int s = 2; s <= 4; ++s) {
+                if (p.n_v < (int64_t)s * 8 * 64) break;
+                const double cost = (double)(rounds - extra) + (double)((cut * s + n_cu - 1) / n_cu) / s + 0.02 * cut / n_cu;
+                if (cost < best - 1e-9) { best = cost; split = s; n_cut = cut; }
+            }
+        }
+    }
     p.split = split;
     p.n_full = (int)n_tiles;
     p.part_keys = 0;
@@ -529,20 +538,20 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     p.part_lse = nullptr;
     int64_t items = n_tiles;
     if (split > 1) {
-        p.n_full = (int)(n_tiles - rem);
+        p.n_full = (int)(n_tiles - n_cut);
         p.part_keys = ((p.n_v + split - 1) / split + 63) / 64 * 64;
-        const size_t slots = (size_t)rem * (split - 1);
+        const size_t slots = (size_t)n_cut * (split - 1);
         float* ws = nullptr;
         hipError_t e = attn_workspace(st, slots * (M * D + M) * sizeof(float), &ws);
         if (e != hipSuccess) return e;
         p.part_out = ws;
         p.part_lse = ws + slots * (M * D);
-        items = p.n_full + (int64_t)rem * split;
+        items = p.n_full + n_cut * split;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(512 / NQ), smem, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split <= 1) return e;
-    hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(rem * (M / 8))), dim3(256), 0, st, p, rem);
+    hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(n_cut * (M / 8))), dim3(256), 0, st, p, (int)n_cut);
     return hipGetLastError();
 }
 

@@ -3,7 +3,31 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace pda {
+
+// One-time, per-device launch setup of a kernel that needs more than the default dynamic LDS size:
+// sets the attribute on the current device the first time the kernel is launched there and
+// returns that device's CU count through n_cu.  One instance per kernel (function-local static).
+struct KernelSetup {
+    static constexpr int MAX_DEV = 64;
+    std::atomic<int> cu[MAX_DEV] = {};
+    hipError_t ensure(const void* kern, int smem_bytes, int* n_cu) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool cached = dev >= 0 && dev < MAX_DEV;
+        int v = cached ? cu[dev].load(std::memory_order_acquire) : 0;
+        if (v == 0) {   // two threads may both get here: setting the attribute twice is harmless
+            if ((e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes)) != hipSuccess) return e;
+            if ((e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+            if (cached) cu[dev].store(v, std::memory_order_release);
+        }
+        if (n_cu) *n_cu = v;
+        return hipSuccess;
+    }
+};
 
 // One attention launch over Hg heads of B batches.  Strides are in elements; a head group of a
 // compact [B,H,S,d] tensor is addressed by offsetting the base pointers and keeping the full
