@@ -509,28 +509,23 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
         if (e != hipSuccess) return e;
     }
     // Work plan: one workgroup per CU at a time, so tiles run in rounds of n_cu and a partly
-    // filled last round wastes the rest of the machine.  The tiles of the last round - and, if
-    // that pays, of the full round before it - are cut into `split` key ranges (at most 4, each at
-    // least 8 key tiles long), so that the tail is made of shorter items.  Cost of a plan in
-    // tile-times: whole rounds + ceil(cut tiles * split / n_cu) / split, plus a small charge per
-    // cut tile for the partial stores and the merge pass.
+    // filled last round wastes the rest of the machine.  The tiles of the last round are cut into
+    // `split` key ranges (at most 4, each at least 8 key tiles long), so that the tail is made of
+    // shorter items; they may spill over one round of such items.  Cost of the tail in tile-times:
+    // ceil(rem * split / n_cu) / split, plus a small charge per cut tile for the partial stores
+    // and the merge pass.  (Cutting tiles of earlier, full rounds as well never lowers that cost.)
     p.tiles_per_head = (int)((p.Sq + M - 1) / M);
     const int64_t n_tiles = (int64_t)p.tiles_per_head * BH;
-    const int64_t rounds = n_tiles / n_cu;
     const int rem = (int)(n_tiles % n_cu);
     int split = 1;
-    int64_t n_cut = 0;
     if (rem) {
-        double best = (double)rounds + 1.0;
-        for (int extra = 0; extra <= (rounds > 0 ? 1 : 0); ++extra) {
-            const int64_t cut = rem + (int64_t)extra * n_cu;
-            for (int s = 2; s <= 4; ++s) {
-                if (p.n_v < (int64_t)s * 8 * 64) break;
-                const double cost = (double)(rounds - extra) + (double)((cut * s + n_cu - 1) / n_cu) / s + 0.02 * cut / n_cu;
-                if (cost < best - 1e-9) { best = cost; split = s; n_cut = cut; }
-            }
+        double best = 1.0;
+        for (int s = 2; s <= 4 && p.n_v >= (int64_t)s * 8 * 64; ++s) {
+            const double cost = (double)(((int64_t)rem * s + n_cu - 1) / n_cu) / s + 0.02 * rem / n_cu;
+            if (cost < best - 1e-9) { best = cost; split = s; }
         }
     }
+    const int64_t n_cut = split > 1 ? rem : 0;
     p.split = split;
     p.n_full = (int)n_tiles;
     p.part_keys = 0;

@@ -141,3 +141,33 @@ def test_c3_masked_group_sampled_rows():
         ro, rl = attention_head(q[0, h], k[0, h], v[0, h], w.scale, w.kv_valid_len, rows=rows)
         e = assert_close(o[0, h][rows], l[0, h][rows], ro, rl, f"C3 head {h}")
         print("C3 head", h, e)
+
+
+def test_seeded_shape_sweep():
+    """Random small and medium shapes (ragged tiles, masks inside and across tiles, several batches,
+    launches whose tail is cut into 2, 3 or 4 key ranges) against the oracle, every element."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    rng = np.random.default_rng(20251112)
+    for case in range(18):
+        d = 128 if case % 6 else 64
+        B = int(rng.integers(1, 3))
+        H = int(rng.integers(1, 6))
+        Sq = int(rng.integers(1, 900))
+        Skv = int(rng.choice([rng.integers(1, 700), rng.integers(1500, 4200)]))
+        n_v = int(rng.choice([Skv, rng.integers(0, Skv + 1), max(0, Skv - int(rng.integers(0, 70)))]))
+        scale = float(rng.choice([d ** -0.5, 0.02, 0.3]))
+        qb, kb, vb = gen_qkv(1000 + case, B, H, Sq, Skv, d, unit_rms=bool(case % 2))
+        q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+        out = torch.full((B, H, Sq, d), float("nan"), device="cuda")
+        lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+        print("sweep case", case, dict(B=B, H=H, Sq=Sq, Skv=Skv, n_v=n_v, d=d, scale=scale), flush=True)
+        pda.attn_fwd(q, k, v, out, lse, scale, n_v)
+        torch.cuda.synchronize()
+        ro, rl = attention(qb, kb, vb, scale, n_v)
+        o, l = out.cpu().numpy(), lse.cpu().numpy()
+        if n_v == 0:
+            assert (o == 0).all() and np.isneginf(l).all()
+        else:
+            assert_close(o, l, ro, rl, f"sweep case {case}")
