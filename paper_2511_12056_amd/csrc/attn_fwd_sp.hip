@@ -18,9 +18,9 @@
 // written slot by slot in issue order (a scheduling barrier after every slot keeps that order).
 // The O accumulators are rescaled after the stream (PV(t-1) has to land first) and only when the
 // running max of some lane moved by more than 2^8: otherwise the old reference is kept, which is
-// exact because the final normalisation uses the same reference.  The row sum is taken over the
-// bf16-rounded probabilities (v_dot2c_f32_bf16, two per instruction), so the weights that reach
-// the PV product sum to exactly the normaliser.
+// exact because the final normalisation uses the same reference.  The row sum is taken with plain
+// fp32 adds on the unrounded probabilities; the dot-product instructions (v_dot2c_f32_bf16), which
+// would sum two rounded ones at a time, occupy the matrix pipe and stall the MFMA stream.
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), four buffers per
 // tensor; the loop is unrolled four times so that every buffer offset is an immediate.  At the
@@ -332,49 +332,77 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         };
 
         // Softmax of tile t, slice by slice (anchored with empty asm statements: pure arithmetic
-        // would otherwise drift out of the slot it is written in).  Measured alternatives - four
-        // max chains, separate FMA / exp / pack / sum stages a slot apart, pre-scaled Q with
-        // exp-only slices - were not faster on this hardware and the last one costs accuracy.
-        float mx[NQ], mc_new[NQ], alpha[NQ], lsum[NQ];
+        // would otherwise drift out of the slot it is written in).
+        float mx[NQ], mx2[NQ], mc_new[NQ], alpha[NQ], lsum[NQ], lsum2[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
             mx[nq] = s_c[nq][0][0];
-            mc_new[nq] = 0.f; alpha[nq] = 1.f; lsum[nq] = 0.f;
+            mx2[nq] = s_c[nq][0][1];
+            mc_new[nq] = 0.f; alpha[nq] = 1.f; lsum[nq] = 0.f; lsum2[nq] = 0.f;
         }
-        auto pack_pair = [&](auto qidx, auto nq_c) {     // pair q = elements 2q, 2q+1 of the 32 this lane holds
-            constexpr int q = decltype(qidx)::value, nq = decltype(nq_c)::value;
-            constexpr int kb = q / 8, u = (q % 8) / 4, j = q % 4;
-            unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
-            asm volatile("" : "+v"(pk));
-            p_io[nq][kb][u][j] = pk;
-            // row sum over the ROUNDED probabilities, two per instruction (v_dot2c_f32_bf16)
-            lsum[nq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
-                                                       __builtin_bit_cast(bf16x2, 0x3f803f80u), lsum[nq], false);
-            asm volatile("" : "+v"(lsum[nq]));
+        // Elements of the lane's 32 scores handled by exponential slot k (0..25): [e_lo(k), e_lo(k+1)).
+        // The work on an element is spread over consecutive slots so that no instruction needs a
+        // result produced in its own slot: slot k-1 forms z = s*c - m, slot k takes exp2(z), slot k+1
+        // adds it to the row sum and, once both halves of a pair exist, packs the pair to bf16.
+        auto e_lo = [](int k) constexpr { return k <= 0 ? 0 : (k >= 26 ? 32 : k * 32 / 26); };
+        auto fma_of = [&](auto kc, auto nq_c) {
+            constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+            static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
+                constexpr int e = decltype(ec)::value;
+                float z = __builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]);
+                asm volatile("" : "+v"(z));
+                s_c[nq][e / 16][e % 16] = z;
+            });
+        };
+        auto exp_of = [&](auto kc, auto nq_c) {
+            constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+            static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
+                constexpr int e = decltype(ec)::value;
+                float pe = __builtin_amdgcn_exp2f(s_c[nq][e / 16][e % 16]);
+                asm volatile("" : "+v"(pe));
+                s_c[nq][e / 16][e % 16] = pe;
+            });
+        };
+        auto sum_pack_of = [&](auto kc, auto nq_c) {
+            constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+            static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
+                constexpr int e = decltype(ec)::value;
+                // row sum with plain adds, two chains (the dot-product instructions would take two
+                // values at a time, but they occupy the matrix pipe and stall the MFMA stream)
+                if constexpr (e % 2 == 0) {
+                    lsum[nq] += s_c[nq][e / 16][e % 16];
+                    asm volatile("" : "+v"(lsum[nq]));
+                } else {
+                    lsum2[nq] += s_c[nq][e / 16][e % 16];
+                    asm volatile("" : "+v"(lsum2[nq]));
+                    constexpr int q = e / 2, kb = q / 8, u = (q % 8) / 4, j = q % 4;   // pair q = elements 2q, 2q+1
+                    unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
+                    asm volatile("" : "+v"(pk));
+                    p_io[nq][kb][u][j] = pk;
+                }
+            });
         };
         auto valu_slice = [&](auto idx, auto nq_c) {
             constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
-            if constexpr (i < 4) {                                  // row max over the lane's 32 scores
+            if constexpr (i < 4) {                                  // row max over the lane's 32 scores, two chains
 #pragma unroll
-                for (int e = 8 * i; e < 8 * i + 8; e += 2)
-                    mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 1) / 16][(e + 1) % 16]);
+                for (int e = 8 * i; e < 8 * i + 8; e += 4) {
+                    mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 2) / 16][(e + 2) % 16]);
+                    mx2[nq] = fmaxf(fmaxf(mx2[nq], s_c[nq][(e + 1) / 16][(e + 1) % 16]), s_c[nq][(e + 3) / 16][(e + 3) % 16]);
+                }
             } else if constexpr (i == 4) {
                 // Move the reference only if the max grew by more than 2^8 (or there is none yet:
                 // -inf gives an infinite difference; a fully hidden tile gives -inf and no move).
-                const float mxc = pair_max(mx[nq]) * c;
+                const float mxc = pair_max(fmaxf(mx[nq], mx2[nq])) * c;
                 mc_new[nq] = (mxc - mc_run[nq] > 8.0f) ? mxc : mc_run[nq];
             } else if constexpr (i == 5) {
                 alpha[nq] = __builtin_amdgcn_exp2f(mc_run[nq] - mc_new[nq]);      // 1 if unmoved, 0 on the first tile
+                fma_of(std::integral_constant<int, 0>{}, nq_c);
             } else {                                                // 32 exponentials over 26 slots
                 constexpr int k = i - 6;
-                constexpr int h0 = k * 32 / 26, h1 = (k + 1) * 32 / 26;
-                static_for<h0, h1>([&](auto hidx) {
-                    constexpr int e = decltype(hidx)::value;
-                    if constexpr (e % 2 == 0 && e >= 2) pack_pair(std::integral_constant<int, e / 2 - 1>{}, nq_c);
-                    float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]));
-                    asm volatile("" : "+v"(pe));
-                    s_c[nq][e / 16][e % 16] = pe;
-                });
+                exp_of(std::integral_constant<int, k>{}, nq_c);
+                fma_of(std::integral_constant<int, k + 1>{}, nq_c);
+                sum_pack_of(std::integral_constant<int, k - 1>{}, nq_c);
             }
         };
 
@@ -389,8 +417,8 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         });
         static_for<0, NQ>([&](auto nq_c) {
             constexpr int nq = decltype(nq_c)::value;
-            pack_pair(std::integral_constant<int, 15>{}, nq_c);
-            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq]);
+            sum_pack_of(std::integral_constant<int, 25>{}, nq_c);
+            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq] + lsum2[nq]);
             mc_run[nq] = mc_new[nq];
         });
         // =====================================================================================
