@@ -166,6 +166,14 @@ def test_c5_split_merge_720p():
         fo[:, :, off:off + n] = o; fl[:, :, off:off + n] = l
         po.append(fo); pl.append(fl)
     _assert_same_up_to_split(out_q, lse_q, full, lfull)
+    # the same three ranges as bench.py issues them: views of the full tensors, written in place
+    out_s = torch.full_like(full, float("nan")); lse_s = torch.full_like(lfull, float("nan"))
+    for off, n in w.query_ranges:
+        pda.attn_fwd_strided(q[:, :, off:off + n], k, v, out_s[:, :, off:off + n], lse_s[:, :, off:off + n],
+                             w.scale, None, off)
+    torch.cuda.synchronize()
+    assert torch.equal(out_s, out_q) and torch.equal(lse_s, lse_q)
+    del out_s, lse_s
     out_m = torch.empty_like(full); lse_m = torch.empty_like(lfull)
     pda.attn_merge(po, pl, out_m, lse_m)
     torch.cuda.synchronize()
@@ -176,6 +184,13 @@ def test_c5_split_merge_720p():
     for off, n in w.key_chunks:
         o, l = _fwd(q, k[:, :, off:off + n].contiguous(), v[:, :, off:off + n].contiguous(), w.scale)
         po.append(o); pl.append(l)
+    # bench.py's form of the first chunk: key views, no copy
+    o_s = torch.empty_like(full); l_s = torch.empty_like(lfull)
+    off, n = w.key_chunks[1]
+    pda.attn_fwd_strided(q, k[:, :, off:off + n], v[:, :, off:off + n], o_s, l_s, w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o_s, po[1]) and torch.equal(l_s, pl[1])
+    del o_s, l_s
     pda.attn_merge(po, pl, out_m, lse_m)
     torch.cuda.synchronize()
     rel = ((out_m - full).norm() / full.norm()).item()
