@@ -50,7 +50,7 @@ def cpu_baseline(w, qb, kb, vb, target_s=15.0):
     attention_head(qb[0, 0], kb[0, 0], vb[0, 0], w.scale, rows=rows)          # calibration
     per_row = (time.perf_counter() - t0) / len(rows)
     n = int(min(w.Sq, max(512, target_s / max(per_row, 1e-9))))
-    n = min(n, 16384)
+    n = min(n, 65536)
     rows = np.linspace(0, w.Sq - 1, n).astype(np.int64)
     t0 = time.perf_counter()
     attention_head(qb[0, 0], kb[0, 0], vb[0, 0], w.scale, rows=rows)

@@ -135,6 +135,7 @@ def test_c4_headchunk_720p():
           "TFLOP/s", round(w.flops / (tms * 1e-3) * 1e-12, 1))
     assert len(gms) == 8
     assert torch.equal(sink, out)
+    assert sum(gms) <= tms * 1.01 + 0.2                     # groups run back to back inside the total
     full, lfull = _fwd(q, k, v, w.scale)                     # one launch over all 24 heads
     torch.cuda.synchronize()
     _assert_same_up_to_split(out, lse, full, lfull)
