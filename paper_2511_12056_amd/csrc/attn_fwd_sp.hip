@@ -16,10 +16,16 @@
 //     LDS reads:     MFMA operand fragments, issued PF slots ahead of their use
 //
 // written slot by slot in issue order (a scheduling barrier after every slot keeps that order).
-// The O accumulators are rescaled after the stream (PV(t-1) has to land first) and only when the
-// running max of some lane moved by more than 2^8: otherwise the old reference is kept, which is
-// exact because the final normalisation uses the same reference.  The row sum is taken with plain
-// fp32 adds on the unrounded probabilities; the dot-product instructions (v_dot2c_f32_bf16), which
+//
+// Softmax reference.  The value of softmax does not depend on the reference that is subtracted
+// before the exponential, only overflow and underflow do, and fp32 (and bf16, which shares its
+// exponent range) leaves a wide margin.  The item is therefore first swept with a FIXED reference per
+// row, the max of the row's scores in the first key tile: no max pass, no rescaling of O, weights
+// may exceed 1.  If a row's sum ends up beyond 2^64 (some later score lay that far above the
+// first tile, or the input held non-finite values) the workgroup sweeps the item again with the
+// usual running max, where the reference moves only when the max grew by more than 2^8 and O is
+// rescaled after the stream in a rare wave-uniform branch.  The row sum is taken with plain fp32
+// adds on the unrounded probabilities; the dot-product instructions (v_dot2c_f32_bf16), which
 // would sum two rounded ones at a time, occupy the matrix pipe and stall the MFMA stream.
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), four buffers per
@@ -160,19 +166,6 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         for (int j = 0; j < CPW; ++j) issue_chunk(base, off0, lds_tile, tile, j);
     };
 
-    // prologue: K tiles 0..3, V tiles 0..1; V buffer 3 (read by the first, all-zero-weight PV) is zeroed
-    issue_tile(kp, ld_offk, K_BASE + 0 * TILE, 0);
-    issue_tile(vp, ld_offv, V_BASE + 0 * TILE, 0);
-    issue_tile(kp, ld_offk, K_BASE + 1 * TILE, 1);
-    issue_tile(kp, ld_offk, K_BASE + 2 * TILE, 2);
-    issue_tile(kp, ld_offk, K_BASE + 3 * TILE, 3);
-    issue_tile(vp, ld_offv, V_BASE + 1 * TILE, 1);
-    {
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < TILE / 16; i += 64 * NW)
-            *reinterpret_cast<u32x4*>(smem + V_BASE + 3 * TILE + i * 16) = z;
-    }
-
     // ---- Q operand fragments, resident for the whole sweep
     bf16x8 qf[NQ][NKK];
 #pragma unroll
@@ -206,22 +199,6 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     // Packed bf16 P (MFMA operand order).  One buffer serves two consecutive tiles: group (kb,u) of
     // tile t-1 is consumed by the PV MFMAs of slots 4(2kb+u)..+3, before the softmax of tile t writes it.
     unsigned p_io[NQ][NKB][2][4];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        mc_run[nq] = -INFINITY;
-        l_run[nq] = 0.f;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o_acc[nq][db][r] = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) p_io[nq][kb][u][j] = 0u;
-    }
-
     const float c = p.scale_log2e;   // > 0 (the host substitutes a tiny positive value for scale 0)
 
     auto mask_tail = [&](f32x16 (&s)[NQ][NKB], int t) {
@@ -241,230 +218,307 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         __builtin_amdgcn_s_barrier();
     };
 
-    // Q fragments and the prologue tiles have arrived
+    // One sweep over the item's keys.  SAFE = false (first attempt): the reference of a row is the
+    // max of its scores in the first key tile and never moves, so the loop carries no max pass and
+    // no rescaling; probabilities may exceed 1.  That is exact as long as nothing overflows, which
+    // the caller of the sweep checks on the row sums.  SAFE = true: running max with lazy updates.
+    auto sweep = [&](auto safe_c) {
+        constexpr bool SAFE = decltype(safe_c)::value;
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
+        for (int nq = 0; nq < NQ; ++nq) {
+            mc_run[nq] = -INFINITY;
+            l_run[nq] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qf[nq][kk]));
-    wait_vmcnt<0>();
-    barrier();
-
-    // ---- S_0 = K_0 Q^T (not overlapped with anything)
-    {
-        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
+                for (int r = 0; r < 16; ++r) o_acc[nq][db][r] = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                const bf16x8 a = *(LDS_PTR(const bf16x8))(k_ptr[kk] + kb * 32 * (D * 2));
+            for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-                for (int nq = 0; nq < NQ; ++nq)
-                    s_a[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nq][kk], kk == 0 ? zero : s_a[nq][kb], 0, 0, 0);
-            }
-        if (BN > n_v) mask_tail(s_a, 0);
-    }
-    barrier();           // K tile 0 is overwritten by the first DMA of the loop
-
-    // One iteration; TB = t % 4 fixes every LDS buffer offset at compile time.
-    //   s_c: scores of tile t (in, overwritten by its probabilities)   s_n: scores of tile t+1 (out)
-    // Slot i (0..31) = the MFMAs fed by operand fragment i (PV fragments 0..15, then QK fragments
-    // 0..15; NQ MFMAs each), the LDS reads of fragment i+PF, and slice i of the softmax VALU work:
-    // slices 0-3 the row max, 4-5 the reference / rescale factors, 6-31 the 32 exponentials with
-    // their packing to bf16 and the row sum.
-    auto iteration = [&](auto tb_c, int t, f32x16 (&s_c)[NQ][NKB], f32x16 (&s_n)[NQ][NKB]) {
-        constexpr int TB = decltype(tb_c)::value;
-        constexpr int KN = (TB + 1) % NBUF;           // buffer of K tile t+1
-        constexpr int VP = (TB + 3) % NBUF;           // buffer of V tile t-1
-        // DMA of this iteration: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last read
-        // in iteration t-1).  Whole tiles take the short path: running scalar tile pointers, fixed
-        // per-lane offsets, LDS destinations as immediates.
-        if ((t + 5) * BN <= n_v) {
-            static_for<0, CPW>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                lds_dma16_at<K_BASE + TB * TILE + j * (NW * 1024)>(k_dma, ld_k[j], dma_base);
-            });
-            static_for<0, CPW>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                lds_dma16_at<V_BASE + ((TB + 2) % NBUF) * TILE + j * (NW * 1024)>(v_dma, ld_v[j], dma_base);
-            });
-        } else {
-            issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
-            issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) p_io[nq][kb][u][j] = 0u;
         }
-        k_dma += BN * D;
-        v_dma += BN * D;
-        constexpr int N_PV = NKB * 2 * NDB, N_QK = NKK * NKB, N_FR = N_PV + N_QK;
-        constexpr int PF = 3, RING = 4;
-        static_assert(N_FR == 32, "slot plan below is written for d = 128 and 64-key tiles");
-        bf16x8 frag[RING];
+        k_dma = kp + 4 * BN * D;
+        v_dma = vp + 2 * BN * D;
+        // prologue: K tiles 0..3, V tiles 0..1; V buffer 3 (read by the first, all-zero-weight PV) is zeroed
+        issue_tile(kp, ld_offk, K_BASE + 0 * TILE, 0);
+        issue_tile(vp, ld_offv, V_BASE + 0 * TILE, 0);
+        issue_tile(kp, ld_offk, K_BASE + 1 * TILE, 1);
+        issue_tile(kp, ld_offk, K_BASE + 2 * TILE, 2);
+        issue_tile(kp, ld_offk, K_BASE + 3 * TILE, 3);
+        issue_tile(vp, ld_offv, V_BASE + 1 * TILE, 1);
+        {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int i = tid; i < TILE / 16; i += 64 * NW)
+                *reinterpret_cast<u32x4*>(smem + V_BASE + 3 * TILE + i * 16) = z;
+        }
+        // the Q fragments (loaded before the first sweep, resident for both) and the prologue tiles have arrived
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qf[nq][kk]));
+        wait_vmcnt<0>();
+        barrier();
 
-        auto load_frag = [&](auto idx) {
-            constexpr int i = decltype(idx)::value;
-            if constexpr (i < N_PV) {
-                constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
-                constexpr int off0 = VP * TILE + (kb * 32 + u * 16) * (D * 2);
-                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0));
-                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0 + 8 * (D * 2)));
-                typedef short s16x8 __attribute__((ext_vector_type(8)));
-                const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                frag[i % RING] = __builtin_bit_cast(bf16x8, av);
-            } else if constexpr (i < N_FR) {
-                constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
-                frag[i % RING] = *(LDS_PTR(const bf16x8))(k_ptr[kk] + (KN * TILE + kb * 32 * (D * 2)));
+        // ---- S_0 = K_0 Q^T (not overlapped with anything)
+        {
+            const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+                for (int kb = 0; kb < NKB; ++kb) {
+                    const bf16x8 a = *(LDS_PTR(const bf16x8))(k_ptr[kk] + kb * 32 * (D * 2));
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        s_a[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nq][kk], kk == 0 ? zero : s_a[nq][kb], 0, 0, 0);
+                }
+            if (BN > n_v) mask_tail(s_a, 0);
+            if constexpr (!SAFE) {
+                // fixed reference: the row max over the first key tile (key 0 is always valid)
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    float m0 = s_a[nq][0][0], m1 = s_a[nq][0][1];
+#pragma unroll
+                    for (int e = 2; e < 32; e += 2) {
+                        m0 = fmaxf(m0, s_a[nq][e / 16][e % 16]);
+                        m1 = fmaxf(m1, s_a[nq][(e + 1) / 16][(e + 1) % 16]);
+                    }
+                    mc_run[nq] = pair_max(fmaxf(m0, m1)) * c;
+                }
             }
-        };
-        auto do_mfma = [&](auto idx, auto nq_c) {
-            constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
-            if constexpr (i < N_PV) {
-                constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
-                const u32x4 pv = {p_io[nq][kb][u][0], p_io[nq][kb][u][1], p_io[nq][kb][u][2], p_io[nq][kb][u][3]};
-                o_acc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], __builtin_bit_cast(bf16x8, pv),
-                                                                        o_acc[nq][db], 0, 0, 0);
+        }
+        barrier();           // K tile 0 is overwritten by the first DMA of the loop
+
+        // One iteration; TB = t % 4 fixes every LDS buffer offset at compile time.
+        //   s_c: scores of tile t (in, overwritten by its probabilities)   s_n: scores of tile t+1 (out)
+        // Slot i (0..31) = the MFMAs fed by operand fragment i (PV fragments 0..15, then QK fragments
+        // 0..15; NQ MFMAs each), the LDS reads of fragment i+PF, and slice i of the softmax VALU work:
+        // slices 0-3 the row max, 4-5 the reference / rescale factors, 6-31 the 32 exponentials with
+        // their packing to bf16 and the row sum.
+        auto iteration = [&](auto tb_c, int t, f32x16 (&s_c)[NQ][NKB], f32x16 (&s_n)[NQ][NKB]) {
+            constexpr int TB = decltype(tb_c)::value;
+            constexpr int KN = (TB + 1) % NBUF;           // buffer of K tile t+1
+            constexpr int VP = (TB + 3) % NBUF;           // buffer of V tile t-1
+            // DMA of this iteration: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last read
+            // in iteration t-1).  Whole tiles take the short path: running scalar tile pointers, fixed
+            // per-lane offsets, LDS destinations as immediates.
+            if ((t + 5) * BN <= n_v) {
+                static_for<0, CPW>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    lds_dma16_at<K_BASE + TB * TILE + j * (NW * 1024)>(k_dma, ld_k[j], dma_base);
+                });
+                static_for<0, CPW>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    lds_dma16_at<V_BASE + ((TB + 2) % NBUF) * TILE + j * (NW * 1024)>(v_dma, ld_v[j], dma_base);
+                });
             } else {
-                constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
-                if constexpr (kk == 0) {
-                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                    s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], zero, 0, 0, 0);
+                issue_tile(kp, ld_offk, K_BASE + TB * TILE, t + 4);
+                issue_tile(vp, ld_offv, V_BASE + ((TB + 2) % NBUF) * TILE, t + 2);
+            }
+            k_dma += BN * D;
+            v_dma += BN * D;
+            constexpr int N_PV = NKB * 2 * NDB, N_QK = NKK * NKB, N_FR = N_PV + N_QK;
+            constexpr int PF = 3, RING = 4;
+            static_assert(N_FR == 32, "slot plan below is written for d = 128 and 64-key tiles");
+            bf16x8 frag[RING];
+
+            auto load_frag = [&](auto idx) {
+                constexpr int i = decltype(idx)::value;
+                if constexpr (i < N_PV) {
+                    constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
+                    constexpr int off0 = VP * TILE + (kb * 32 + u * 16) * (D * 2);
+                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0));
+                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0 + 8 * (D * 2)));
+                    typedef short s16x8 __attribute__((ext_vector_type(8)));
+                    const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    frag[i % RING] = __builtin_bit_cast(bf16x8, av);
+                } else if constexpr (i < N_FR) {
+                    constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
+                    frag[i % RING] = *(LDS_PTR(const bf16x8))(k_ptr[kk] + (KN * TILE + kb * 32 * (D * 2)));
+                }
+            };
+            auto do_mfma = [&](auto idx, auto nq_c) {
+                constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
+                if constexpr (i < N_PV) {
+                    constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
+                    const u32x4 pv = {p_io[nq][kb][u][0], p_io[nq][kb][u][1], p_io[nq][kb][u][2], p_io[nq][kb][u][3]};
+                    o_acc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], __builtin_bit_cast(bf16x8, pv),
+                                                                            o_acc[nq][db], 0, 0, 0);
                 } else {
-                    s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], s_n[nq][kb], 0, 0, 0);
+                    constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
+                    if constexpr (kk == 0) {
+                        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], zero, 0, 0, 0);
+                    } else {
+                        s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], s_n[nq][kb], 0, 0, 0);
+                    }
                 }
-            }
-        };
+            };
 
-        // Softmax of tile t, slice by slice (anchored with empty asm statements: pure arithmetic
-        // would otherwise drift out of the slot it is written in).
-        float mx[NQ], mx2[NQ], mc_new[NQ], alpha[NQ], lsum[NQ], lsum2[NQ];
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            mx[nq] = s_c[nq][0][0];
-            mx2[nq] = s_c[nq][0][1];
-            mc_new[nq] = 0.f; alpha[nq] = 1.f; lsum[nq] = 0.f; lsum2[nq] = 0.f;
-        }
-        // Elements of the lane's 32 scores handled by exponential slot k (0..25): [e_lo(k), e_lo(k+1)).
-        // The work on an element is spread over consecutive slots so that no instruction needs a
-        // result produced in its own slot: slot k-1 forms z = s*c - m, slot k takes exp2(z), slot k+1
-        // adds it to the row sum and, once both halves of a pair exist, packs the pair to bf16.
-        auto e_lo = [](int k) constexpr { return k <= 0 ? 0 : (k >= 26 ? 32 : k * 32 / 26); };
-        auto fma_of = [&](auto kc, auto nq_c) {
-            constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
-            static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
-                constexpr int e = decltype(ec)::value;
-                float z = __builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]);
-                asm volatile("" : "+v"(z));
-                s_c[nq][e / 16][e % 16] = z;
-            });
-        };
-        auto exp_of = [&](auto kc, auto nq_c) {
-            constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
-            static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
-                constexpr int e = decltype(ec)::value;
-                float pe = __builtin_amdgcn_exp2f(s_c[nq][e / 16][e % 16]);
-                asm volatile("" : "+v"(pe));
-                s_c[nq][e / 16][e % 16] = pe;
-            });
-        };
-        auto sum_pack_of = [&](auto kc, auto nq_c) {
-            constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
-            static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
-                constexpr int e = decltype(ec)::value;
-                // row sum with plain adds, two chains (the dot-product instructions would take two
-                // values at a time, but they occupy the matrix pipe and stall the MFMA stream)
-                if constexpr (e % 2 == 0) {
-                    lsum[nq] += s_c[nq][e / 16][e % 16];
-                    asm volatile("" : "+v"(lsum[nq]));
-                } else {
-                    lsum2[nq] += s_c[nq][e / 16][e % 16];
-                    asm volatile("" : "+v"(lsum2[nq]));
-                    constexpr int q = e / 2, kb = q / 8, u = (q % 8) / 4, j = q % 4;   // pair q = elements 2q, 2q+1
-                    unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
-                    asm volatile("" : "+v"(pk));
-                    p_io[nq][kb][u][j] = pk;
-                }
-            });
-        };
-        auto valu_slice = [&](auto idx, auto nq_c) {
-            constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
-            if constexpr (i < 4) {                                  // row max over the lane's 32 scores, two chains
-#pragma unroll
-                for (int e = 8 * i; e < 8 * i + 8; e += 4) {
-                    mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 2) / 16][(e + 2) % 16]);
-                    mx2[nq] = fmaxf(fmaxf(mx2[nq], s_c[nq][(e + 1) / 16][(e + 1) % 16]), s_c[nq][(e + 3) / 16][(e + 3) % 16]);
-                }
-            } else if constexpr (i == 4) {
-                // Move the reference only if the max grew by more than 2^8 (or there is none yet:
-                // -inf gives an infinite difference; a fully hidden tile gives -inf and no move).
-                const float mxc = pair_max(fmaxf(mx[nq], mx2[nq])) * c;
-                mc_new[nq] = (mxc - mc_run[nq] > 8.0f) ? mxc : mc_run[nq];
-            } else if constexpr (i == 5) {
-                alpha[nq] = __builtin_amdgcn_exp2f(mc_run[nq] - mc_new[nq]);      // 1 if unmoved, 0 on the first tile
-                fma_of(std::integral_constant<int, 0>{}, nq_c);
-            } else {                                                // 32 exponentials over 26 slots
-                constexpr int k = i - 6;
-                exp_of(std::integral_constant<int, k>{}, nq_c);
-                fma_of(std::integral_constant<int, k + 1>{}, nq_c);
-                sum_pack_of(std::integral_constant<int, k - 1>{}, nq_c);
-            }
-        };
-
-        // ================= interleaved region: softmax(t) | PV(t-1), QK(t+1) =================
-        static_for<0, PF>([&](auto i) { load_frag(i); });
-        static_for<0, N_FR>([&](auto idx) {
-            constexpr int i = decltype(idx)::value;
-            static_for<0, NQ>([&](auto nq_c) { do_mfma(idx, nq_c); });
-            load_frag(std::integral_constant<int, i + PF>{});
-            static_for<0, NQ>([&](auto nq_c) { valu_slice(idx, nq_c); });
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        static_for<0, NQ>([&](auto nq_c) {
-            constexpr int nq = decltype(nq_c)::value;
-            sum_pack_of(std::integral_constant<int, 25>{}, nq_c);
-            l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq] + lsum2[nq]);
-            mc_run[nq] = mc_new[nq];
-        });
-        // =====================================================================================
-
-        // rescale O once PV(t-1) is in, if some lane moved its reference (rare after the first tiles)
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            if (__builtin_amdgcn_ballot_w64(alpha[nq] != 1.0f) != 0) {
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o_acc[nq][db][r] *= alpha[nq];
-            }
-        }
-        if ((t + 2) * BN > n_v) mask_tail(s_n, t + 1);     // S_{t+1} holds hidden keys
-
-        if constexpr (NQ == 2) {
-            // One wavefront per SIMD owns 512 registers, half of them accumulation registers that
-            // only MFMAs (and loads) can address.  Pin what only MFMAs touch there - the O
-            // accumulators and the Q fragments - so that the VALU-visible half is left for the scores.
+            // Softmax of tile t, slice by slice (anchored with empty asm statements: pure arithmetic
+            // would otherwise drift out of the slot it is written in).
+            float mx[NQ], mx2[NQ], mc_new[NQ], alpha[NQ], lsum[NQ], lsum2[NQ];
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) {
-#pragma unroll
-                for (int db = 0; db < NDB; ++db) asm volatile("" : "+a"(o_acc[nq][db]));
-#pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+a"(qf[nq][kk]));
+                mx[nq] = s_c[nq][0][0];
+                mx2[nq] = s_c[nq][0][1];
+                mc_new[nq] = SAFE ? 0.f : mc_run[nq]; alpha[nq] = 1.f; lsum[nq] = 0.f; lsum2[nq] = 0.f;
             }
-        }
-        // This iteration's DMA batch: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last
-        // read in iteration t-1).  Issued here, where the wavefronts of a workgroup arrive spread
-        // out in time, rather than right after the barrier where all of them would queue up at once.
-        wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
-        barrier();
-    };
+            // Elements of the lane's 32 scores handled by exponential slot k (0..25): [e_lo(k), e_lo(k+1)).
+            // The work on an element is spread over consecutive slots so that no instruction needs a
+            // result produced in its own slot: slot k-1 forms z = s*c - m, slot k takes exp2(z), slot k+1
+            // adds it to the row sum and, once both halves of a pair exist, packs the pair to bf16.
+            // SAFE: slots 0-3 row max, 4-5 reference and rescale factor, 6-31 exponentials.  Otherwise the
+            // exponentials start at slot 3 (not earlier: the packed pair q of this tile may replace that of
+            // the previous tile only after the PV MFMAs of slots 0..3, 4..7, ... have read its group).
+            constexpr int X0 = SAFE ? 6 : 3, NX = 32 - X0;
+            auto e_lo = [](int k) constexpr { return k <= 0 ? 0 : (k >= NX ? 32 : k * 32 / NX); };
+            auto fma_of = [&](auto kc, auto nq_c) {
+                constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+                static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    float z = __builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]);
+                    asm volatile("" : "+v"(z));
+                    s_c[nq][e / 16][e % 16] = z;
+                });
+            };
+            auto exp_of = [&](auto kc, auto nq_c) {
+                constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+                static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    float pe = __builtin_amdgcn_exp2f(s_c[nq][e / 16][e % 16]);
+                    asm volatile("" : "+v"(pe));
+                    s_c[nq][e / 16][e % 16] = pe;
+                });
+            };
+            auto sum_pack_of = [&](auto kc, auto nq_c) {
+                constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+                static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    // row sum with plain adds, two chains (the dot-product instructions would take two
+                    // values at a time, but they occupy the matrix pipe and stall the MFMA stream)
+                    if constexpr (e % 2 == 0) {
+                        lsum[nq] += s_c[nq][e / 16][e % 16];
+                        asm volatile("" : "+v"(lsum[nq]));
+                    } else {
+                        lsum2[nq] += s_c[nq][e / 16][e % 16];
+                        asm volatile("" : "+v"(lsum2[nq]));
+                        constexpr int q = e / 2, kb = q / 8, u = (q % 8) / 4, j = q % 4;   // pair q = elements 2q, 2q+1
+                        unsigned pk = pack_bf16(s_c[nq][kb][8 * u + 2 * j], s_c[nq][kb][8 * u + 2 * j + 1]);
+                        asm volatile("" : "+v"(pk));
+                        p_io[nq][kb][u][j] = pk;
+                    }
+                });
+            };
+            auto valu_slice = [&](auto idx, auto nq_c) {
+                constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
+                if constexpr (SAFE && i < 4) {                          // row max over the lane's 32 scores, two chains
+#pragma unroll
+                    for (int e = 8 * i; e < 8 * i + 8; e += 4) {
+                        mx[nq] = fmaxf(fmaxf(mx[nq], s_c[nq][e / 16][e % 16]), s_c[nq][(e + 2) / 16][(e + 2) % 16]);
+                        mx2[nq] = fmaxf(fmaxf(mx2[nq], s_c[nq][(e + 1) / 16][(e + 1) % 16]), s_c[nq][(e + 3) / 16][(e + 3) % 16]);
+                    }
+                } else if constexpr (SAFE && i == 4) {
+                    // Move the reference only if the max grew by more than 2^8 (or there is none yet:
+                    // -inf gives an infinite difference; a fully hidden tile gives -inf and no move).
+                    const float mxc = pair_max(fmaxf(mx[nq], mx2[nq])) * c;
+                    mc_new[nq] = (mxc - mc_run[nq] > 8.0f) ? mxc : mc_run[nq];
+                } else if constexpr (SAFE && i == 5) {
+                    alpha[nq] = __builtin_amdgcn_exp2f(mc_run[nq] - mc_new[nq]);      // 1 if unmoved, 0 on the first tile
+                    fma_of(std::integral_constant<int, 0>{}, nq_c);
+                } else if constexpr (!SAFE && i == X0 - 1) {
+                    fma_of(std::integral_constant<int, 0>{}, nq_c);
+                } else if constexpr (i >= X0) {                         // 32 exponentials over NX slots
+                    constexpr int k = i - X0;
+                    exp_of(std::integral_constant<int, k>{}, nq_c);
+                    fma_of(std::integral_constant<int, k + 1>{}, nq_c);
+                    sum_pack_of(std::integral_constant<int, k - 1>{}, nq_c);
+                }
+            };
 
-    // The loop runs over tiles 0 .. nt (the extra one only completes PV(nt-1): its scores are all
-    // hidden, so its probabilities are zero), rounded up to a multiple of four so that buffer
-    // offsets are immediates and the score / probability registers alternate roles without copies.
-    const int t_end = (nt + 4) & ~3;
-    for (int t = 0; t < t_end; t += 4) {
-        iteration(std::integral_constant<int, 0>{}, t, s_a, s_b);
-        iteration(std::integral_constant<int, 1>{}, t + 1, s_b, s_a);
-        iteration(std::integral_constant<int, 2>{}, t + 2, s_a, s_b);
-        iteration(std::integral_constant<int, 3>{}, t + 3, s_b, s_a);
+            // ================= interleaved region: softmax(t) | PV(t-1), QK(t+1) =================
+            static_for<0, PF>([&](auto i) { load_frag(i); });
+            static_for<0, N_FR>([&](auto idx) {
+                constexpr int i = decltype(idx)::value;
+                static_for<0, NQ>([&](auto nq_c) { do_mfma(idx, nq_c); });
+                load_frag(std::integral_constant<int, i + PF>{});
+                static_for<0, NQ>([&](auto nq_c) { valu_slice(idx, nq_c); });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            static_for<0, NQ>([&](auto nq_c) {
+                constexpr int nq = decltype(nq_c)::value;
+                sum_pack_of(std::integral_constant<int, NX - 1>{}, nq_c);
+                if constexpr (SAFE) {
+                    l_run[nq] = __builtin_fmaf(l_run[nq], alpha[nq], lsum[nq] + lsum2[nq]);
+                    mc_run[nq] = mc_new[nq];
+                } else {
+                    l_run[nq] += lsum[nq] + lsum2[nq];
+                }
+            });
+            // =====================================================================================
+
+            // rescale O once PV(t-1) is in, if some lane moved its reference (rare after the first tiles)
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+                if (SAFE && __builtin_amdgcn_ballot_w64(alpha[nq] != 1.0f) != 0) {
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) o_acc[nq][db][r] *= alpha[nq];
+                }
+            }
+            if ((t + 2) * BN > n_v) mask_tail(s_n, t + 1);     // S_{t+1} holds hidden keys
+
+            if constexpr (NQ == 2) {
+                // One wavefront per SIMD owns 512 registers, half of them accumulation registers that
+                // only MFMAs (and loads) can address.  Pin what only MFMAs touch there - the O
+                // accumulators and the Q fragments - so that the VALU-visible half is left for the scores.
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db) asm volatile("" : "+a"(o_acc[nq][db]));
+#pragma unroll
+                    for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+a"(qf[nq][kk]));
+                }
+            }
+            // This iteration's DMA batch: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last
+            // read in iteration t-1).  Issued here, where the wavefronts of a workgroup arrive spread
+            // out in time, rather than right after the barrier where all of them would queue up at once.
+            wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
+            barrier();
+        };
+
+        // The loop runs over tiles 0 .. nt (the extra one only completes PV(nt-1): its scores are all
+        // hidden, so its probabilities are zero), rounded up to a multiple of four so that buffer
+        // offsets are immediates and the score / probability registers alternate roles without copies.
+        const int t_end = (nt + 4) & ~3;
+        for (int t = 0; t < t_end; t += 4) {
+            iteration(std::integral_constant<int, 0>{}, t, s_a, s_b);
+            iteration(std::integral_constant<int, 1>{}, t + 1, s_b, s_a);
+            iteration(std::integral_constant<int, 2>{}, t + 2, s_a, s_b);
+            iteration(std::integral_constant<int, 3>{}, t + 3, s_b, s_a);
+        }
+        wait_vmcnt<0>();        // no DMA may outlive the workgroup's LDS
+    };
+    sweep(std::false_type{});
+    {
+        // A row whose sum left the safe range (a later score exceeded the first tile's max by more
+        // than ~2^64, or non-finite input) makes the whole workgroup redo the item with the running max.
+        bool bad = false;
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) bad |= !(pair_sum(l_run[nq]) < 1.8446744e19f);
+        const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
+        barrier();                                   // every wavefront is done with the LDS tiles and its DMA
+        LDS_PTR(volatile int) flags = (LDS_PTR(volatile int))smem;
+        if (lane == 0) flags[wave] = wave_bad ? 1 : 0;
+        barrier();
+        int any = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) any |= flags[w];
+        barrier();                                   // flags are read before the redo's DMA reuses their bytes
+        if (__builtin_amdgcn_readfirstlane(any)) sweep(std::true_type{});
     }
-    wait_vmcnt<0>();        // no DMA may outlive the workgroup's LDS
 
     // ---- epilogue: normalise, write out and lse
 #pragma unroll

@@ -171,3 +171,30 @@ def test_seeded_shape_sweep():
             assert (o == 0).all() and np.isneginf(l).all()
         else:
             assert_close(o, l, ro, rl, f"sweep case {case}")
+
+
+def test_scores_far_above_the_first_tile_take_the_running_max_path():
+    """The kernel's first attempt keeps the max of a row's first key tile as its only reference; rows
+    whose later scores exceed it by more than ~2^64 (in powers of two) would overflow and must be
+    recomputed with the running max.  Keys beyond the first tile score hundreds to thousands above
+    it here, for some rows only, in some heads only, and once in the middle of a tile sweep."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    rng = np.random.default_rng(77)
+    B, H, Sq, Skv, d = 1, 3, 600, 1500, 128
+    q = rng.standard_normal((B, H, Sq, d)).astype(np.float32)
+    k = (rng.standard_normal((B, H, Skv, d)) * 0.01).astype(np.float32)
+    v = rng.standard_normal((B, H, Skv, d)).astype(np.float32)
+    k[:, 0, 300:] *= 3000.0                      # head 0: every key after the 4th tile is huge for every row
+    k[0, 1, 1111] = q[0, 1, 5] * 40.0            # head 1: one outlier key aligned with query row 5
+    # head 2: ordinary
+    qb, kb, vb = f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v)
+    for n_v in (Skv, 1200):
+        out = torch.full((B, H, Sq, d), float("nan"), device="cuda")
+        lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+        pda.attn_fwd(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out, lse, 1.0, n_v)
+        torch.cuda.synchronize()
+        ro, rl = attention(qb, kb, vb, 1.0, n_v)
+        assert np.abs(rl).max() > 500                                   # the inputs do what they are meant to
+        assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, f"overflow redo n_v={n_v}")
