@@ -1,8 +1,10 @@
 // Flash-attention forward, software-pipelined schedule for gfx950, d = 128, 64-key tiles,
 // 256 query rows per workgroup.  Template parameter NQ = number of 32-row query sub-tiles a
-// wavefront owns.  Only NQ = 1 (8 wavefronts, two per SIMD) is instantiated: NQ = 2 (one
-// wavefront per SIMD, each K/V operand fragment feeding two MFMAs, which would halve the LDS
-// return traffic) needs more ordinary VGPRs than the 256 a wavefront can address and spills.
+// wavefront owns.  Only NQ = 1 (8 wavefronts, two per SIMD) is instantiated.  NQ = 2 (one wavefront
+// per SIMD, each K/V operand fragment feeding two MFMAs, half the LDS operand reads) needs the O
+// accumulators and Q fragments in accumulation registers, which the compiler only does when the
+// MFMAs are written in assembly; built that way it was slower (a single wavefront per SIMD leaves
+// the latencies at the iteration boundary exposed).
 //
 // MFMA formulation and LDS tile layout are those of attn_fwd.hip (S^T = K Q^T, O^T = V^T P^T on
 // v_mfma_f32_32x32x16_bf16, one query per lane, XOR-swizzled 16-byte granules).  Schedule: on
