@@ -30,7 +30,8 @@ int hip_fail(hipError_t e, const char* what) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Tiling variant of the forward kernel; PDA_ATTN_VARIANT in the environment overrides the default
-// (a tuning aid: every variant computes the same function).
+// (a tuning and testing aid: every variant computes the same function; 1, 2 = reference tilings,
+// 3 = default kernel with its running-max sweep forced on every item).
 int attn_variant() {
     static int v = [] {
         const char* s = getenv("PDA_ATTN_VARIANT");

@@ -316,6 +316,11 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipS
     switch (variant) {
         case 1:  return launch_variant<128, 1, 4, 64, 2>(p, BH, st);   // reference tiling, M=128, two workgroups per CU
         case 2:  return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // reference tiling, M=256, two waves per SIMD
+        case 3: {                                                      // software-pipelined kernel, second sweep forced
+            AttnParams r = p;
+            r.redo_always = 1;
+            return launch_attn_fwd_sp(r, BH, st);
+        }
         default: return launch_attn_fwd_sp(p, BH, st);                 // software-pipelined kernel
     }
 }

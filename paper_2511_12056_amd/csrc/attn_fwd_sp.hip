@@ -507,7 +507,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     {
         // A row whose sum left the safe range (a later score exceeded the first tile's max by more
         // than ~2^64, or non-finite input) makes the whole workgroup redo the item with the running max.
-        bool bad = false;
+        bool bad = p.redo_always != 0;               // test switch: every item takes the second sweep
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) bad |= !(pair_sum(l_run[nq]) < 1.8446744e19f);
         const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;

@@ -58,6 +58,7 @@ struct AttnParams {
     int64_t part_keys;
     float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
     float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
+    int redo_always;        // software-pipelined kernel: sweep every item a second time with the running max (testing aid)
 };
 
 // Enqueue the forward kernel for B*Hg = BH (batch, head) pairs.  variant selects a tiling (0 = default).

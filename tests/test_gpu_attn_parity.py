@@ -198,3 +198,43 @@ def test_scores_far_above_the_first_tile_take_the_running_max_path():
         ro, rl = attention(qb, kb, vb, 1.0, n_v)
         assert np.abs(rl).max() > 500                                   # the inputs do what they are meant to
         assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, f"overflow redo n_v={n_v}")
+
+
+def test_reference_tilings_and_forced_second_sweep_agree_with_the_oracle(tmp_path):
+    """PDA_ATTN_VARIANT selects the reference tilings (1, 2) or forces the default kernel's
+    running-max sweep on every item (3).  The switch is read once per process, so each variant runs
+    in a small child process; its results are checked here against the oracle."""
+    import subprocess
+    import sys
+    from oracle import attention
+    shapes = [(1, 2, 515, 1100, 1050, 0.09), (2, 1, 300, 4200, 4200, 0.3), (1, 3, 777, 64, 40, 0.0883883)]
+    child = r'''
+import sys, numpy as np, torch
+sys.path.insert(0, sys.argv[1])
+import paper_2511_12056_amd as pda
+from synth import gen_qkv
+from tests.util import to_dev_bf16
+shapes = eval(sys.argv[3])
+res = {}
+for i, (B, H, Sq, Skv, n_v, scale) in enumerate(shapes):
+    qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, 128, unit_rms=bool(i % 2))
+    out = torch.full((B, H, Sq, 128), float("nan"), device="cuda"); lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+    pda.attn_fwd(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out, lse, scale, n_v)
+    torch.cuda.synchronize()
+    res[f"o{i}"] = out.cpu().numpy(); res[f"l{i}"] = lse.cpu().numpy()
+np.savez(sys.argv[2], **res)
+'''
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    refs = []
+    for i, (B, H, Sq, Skv, n_v, scale) in enumerate(shapes):
+        qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, 128, unit_rms=bool(i % 2))
+        refs.append(attention(qb, kb, vb, scale, n_v))
+    for variant in ("1", "2", "3"):
+        f = str(tmp_path / f"v{variant}.npz")
+        env = dict(os.environ, PDA_ATTN_VARIANT=variant)
+        print("variant", variant, flush=True)
+        subprocess.run([sys.executable, "-c", child, root, f, repr(shapes)], check=True, env=env, timeout=200)
+        got = np.load(f)
+        for i, (ro, rl) in enumerate(refs):
+            assert_close(got[f"o{i}"], got[f"l{i}"], ro, rl, f"variant {variant} shape {i}")
