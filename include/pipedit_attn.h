@@ -91,6 +91,19 @@ int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out
                          float scale, int64_t kv_valid_len, int64_t q_offset, void* stream);
 
 /*
+ * pda_attn_fwd for callers that fold the softmax scale into Q where Q is produced (for instance
+ * pda_pack_heads with premul = scale * log2(e), which costs no extra rounding there): the scores
+ * s_j = <q_i, k_j> are taken to be in units of log2, i.e.
+ *
+ *     lse_i = ln sum_j 2^(s_j),      out_i = sum_j 2^(s_j) v_j / sum_j 2^(s_j)
+ *
+ * which is pda_attn_fwd with scale = ln 2 evaluated exactly.  The kernel then needs no arithmetic
+ * between the matrix product and the exponential.  Arguments as pda_attn_fwd.
+ */
+int pda_attn_fwd_base2(const void* q, const void* k, const void* v, float* out, float* lse,
+                       int B, int H, int64_t Sq, int64_t Skv, int d, int64_t kv_valid_len, void* stream);
+
+/*
  * Exact merge of n partial attentions computed over disjoint key sets (the
  * recombination a Ring-Attention style key split needs, and what re-joins
  * query ranges when each range is embedded in a full-length partial whose
@@ -196,10 +209,12 @@ int pda_headchunk_run_ex(const void* q, const void* k, const void* v, float* out
  * Pre-attention pack: token-major fp32 projections x [B,S,H,d] (one row of H*d features per
  * token) to the head-major bf16 tensor y [B,H,S,d] that Algorithm 1 slices per head.  With
  * unit_rms != 0 every d-vector is first divided by its own root mean square (fp32 arithmetic;
- * a zero vector stays zero).  Rounding to bf16 is to nearest even.  d must be 64 or 128;
- * x and y 16-byte aligned and distinct; B*S*H == 0 is a no-op.
+ * a zero vector stays zero).  Every element is multiplied by premul (finite; 1 for none) before
+ * the one rounding to bf16 (nearest even): a Q packed with premul = scale * log2(e) goes with
+ * pda_attn_fwd_base2.  d must be 64 or 128; x and y 16-byte aligned and distinct; B*S*H == 0 is
+ * a no-op.
  */
-int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, void* stream);
+int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, float premul, void* stream);
 
 /*
  * Planner formulas (host only; every pointer below is a HOST pointer; no device work).

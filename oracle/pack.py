@@ -8,7 +8,10 @@ rounds it to bf16; with unit_rms it first divides the vector by its own root
 mean square (the per-head query/key normalisation of the synthetic workloads:
 no mean subtraction, no gain, no epsilon).  A zero vector stays zero.
 
-    y[b, h, s, :] = bf16( x[b, s, h, :] / sqrt(mean_c x[b, s, h, c]^2) )
+    y[b, h, s, :] = bf16( premul * x[b, s, h, :] / sqrt(mean_c x[b, s, h, c]^2) )
+
+premul (default 1) lets the producer of Q fold the softmax scale, times log2(e), into Q before
+the one rounding, so that the attention kernel can take the scores as exponents of 2.
 
 Evaluated in fp64 and rounded ONCE to bf16 (nearest, ties to even).  The kernel
 works in fp32, so a result that lies within fp32 rounding of a bf16 rounding
@@ -29,10 +32,11 @@ def round_to_bf16(y: np.ndarray) -> np.ndarray:
     return np.ldexp(np.rint(m * 256.0) / 256.0, e)        # rint rounds half to even
 
 
-def pack_heads(x: np.ndarray, unit_rms: bool) -> np.ndarray:
-    """x [B,S,H,d] (any float dtype) -> bf16 values as fp64, [B,H,S,d]."""
+def pack_heads(x: np.ndarray, unit_rms: bool, premul: float = 1.0) -> np.ndarray:
+    """x [B,S,H,d] (any float dtype) -> bf16 values as fp64, [B,H,S,d]; premul multiplies before the rounding."""
     x = np.asarray(x, dtype=np.float64)
     if unit_rms:
         rms = np.sqrt(np.mean(x * x, axis=-1, keepdims=True))
         x = np.divide(x, rms, out=np.zeros_like(x), where=rms > 0)
+    x = x * float(premul)
     return round_to_bf16(np.ascontiguousarray(x.transpose(0, 2, 1, 3)))

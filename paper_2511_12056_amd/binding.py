@@ -49,7 +49,9 @@ def _load() -> C.CDLL:
     lib.pda_headchunk_run_ex.restype = i32
     lib.pda_pipesp_postprocess.argtypes = [C.POINTER(vp), i32, i32, i64, fp, i64, i32, vp]
     lib.pda_pipesp_postprocess.restype = i32
-    lib.pda_pack_heads.argtypes = [fp, vp, i32, i64, i32, i32, i32, vp]
+    lib.pda_pack_heads.argtypes = [fp, vp, i32, i64, i32, i32, i32, f32, vp]
+    lib.pda_attn_fwd_base2.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, i64, vp]
+    lib.pda_attn_fwd_base2.restype = i32
     lib.pda_pack_heads.restype = i32
     f64 = C.c_double
     lib.pda_plan_n_decode.argtypes = [f64, f64, i32, C.POINTER(i32)]
@@ -117,6 +119,22 @@ def attn_fwd(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None
     n_v = Skv if kv_valid_len is None else int(kv_valid_len)
     _check(lib.pda_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
                             n_v, int(q_offset), _stream_handle(stream)))
+    return out, lse
+
+
+def attn_fwd_base2(q, k, v, out, lse, kv_valid_len: Optional[int] = None, stream=None):
+    """pda_attn_fwd_base2: as attn_fwd with the scores q.k already in log2 units (weights 2^(q.k))."""
+    import torch
+    B, H, Sq, d = q.shape
+    Skv = k.shape[2]
+    _expect(q, torch.bfloat16, (B, H, Sq, d), "q")
+    _expect(k, torch.bfloat16, (B, H, Skv, d), "k")
+    _expect(v, torch.bfloat16, (B, H, Skv, d), "v")
+    _expect(out, torch.float32, (B, H, Sq, d), "out")
+    _expect(lse, torch.float32, (B, H, Sq), "lse")
+    n_v = Skv if kv_valid_len is None else int(kv_valid_len)
+    _check(lib.pda_attn_fwd_base2(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, n_v,
+                                  _stream_handle(stream)))
     return out, lse
 
 
@@ -257,13 +275,13 @@ def pipesp_postprocess(chunks: Sequence, h: int, n: int, hidden, chunk_row_strid
     return hidden
 
 
-def pack_heads(x, y, unit_rms: bool, stream=None):
-    """pda_pack_heads: x [B,S,H,d] fp32 -> y [B,H,S,d] bf16."""
+def pack_heads(x, y, unit_rms: bool, premul: float = 1.0, stream=None):
+    """pda_pack_heads: x [B,S,H,d] fp32 -> y [B,H,S,d] bf16 (every element times premul before rounding)."""
     import torch
     B, S, H, d = x.shape
     _expect(x, torch.float32, (B, S, H, d), "x")
     _expect(y, torch.bfloat16, (B, H, S, d), "y")
-    _check(lib.pda_pack_heads(_ptr(x), _ptr(y), B, S, H, d, 1 if unit_rms else 0, _stream_handle(stream)))
+    _check(lib.pda_pack_heads(_ptr(x), _ptr(y), B, S, H, d, 1 if unit_rms else 0, float(premul), _stream_handle(stream)))
     return y
 
 

@@ -70,8 +70,10 @@ Strides compact_strides(int H, int64_t Sq, int64_t Skv, int d) {
 }
 
 // Launch attention for hg heads of B batches; the pointers address the first of those heads.
+// base2: the scores q.k are already in log2 units (scale is then ln 2 and is not applied again).
 hipError_t launch_strided(const void* q, const void* k, const void* v, float* out, float* lse,
-                          int B, int hg, int64_t Sq, int d, const Strides& s, float scale, int64_t n_v, hipStream_t st) {
+                          int B, int hg, int64_t Sq, int d, const Strides& s, float scale, int64_t n_v, hipStream_t st,
+                          bool base2 = false) {
     pda::AttnParams p{};
     p.q = static_cast<const __bf16*>(q);
     p.k = static_cast<const __bf16*>(k);
@@ -87,7 +89,8 @@ hipError_t launch_strided(const void* q, const void* k, const void* v, float* ou
     p.Hg = hg;
     p.scale = scale;
     // scale 0 is run with a tiny positive factor so that hidden keys (-inf scores) still get exp2(-inf) = 0
-    p.scale_log2e = std::fmax(scale * 1.4426950408889634f, 1e-37f);
+    p.scale_log2e = base2 ? 1.0f : std::fmax(scale * 1.4426950408889634f, 1e-37f);
+    p.base2 = base2 ? 1 : 0;
     return pda::launch_attn_fwd(p, B * hg, d, attn_variant(), st);
 }
 
@@ -235,6 +238,18 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
     return PDA_OK;
 }
 
+int pda_attn_fwd_base2(const void* q, const void* k, const void* v, float* out, float* lse,
+                       int B, int H, int64_t Sq, int64_t Skv, int d, int64_t kv_valid_len, void* stream) {
+    const float ln2 = 0.6931471805599453f;
+    int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, ln2, kv_valid_len);
+    if (rc != PDA_OK) return rc;
+    if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
+    hipError_t e = launch_strided(q, k, v, out, lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d), ln2, kv_valid_len,
+                                  static_cast<hipStream_t>(stream), true);
+    if (e != hipSuccess) return hip_fail(e, "attention launch");
+    return PDA_OK;
+}
+
 int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out, float* lse,
                          int B, int H, int64_t Sq, int64_t Skv, int d,
                          int64_t q_batch_stride, int64_t q_head_stride,
@@ -366,7 +381,7 @@ int pda_pipesp_postprocess(const float* const* chunks, int h, int n, int64_t chu
     return PDA_OK;
 }
 
-int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, void* stream) {
+int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, float premul, void* stream) {
     if (B < 0 || H < 0 || S < 0) return fail(PDA_ERR_INVALID_ARG, "negative size (B=%d H=%d S=%lld)", B, H, (long long)S);
     if (d != 64 && d != 128) return fail(PDA_ERR_UNSUPPORTED, "head dim d=%d not supported (64 or 128)", d);
     if ((double)B * H * (double)S * d >= 1099511627776.0) return fail(PDA_ERR_UNSUPPORTED, "B*H*S*d overflows 2^40 elements");
@@ -374,7 +389,8 @@ int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int 
     if (!x || !y) return fail(PDA_ERR_INVALID_ARG, "null x/y");
     if (!aligned16(x) || !aligned16(y)) return fail(PDA_ERR_UNSUPPORTED, "x and y must be 16-byte aligned");
     if (static_cast<const void*>(x) == y) return fail(PDA_ERR_INVALID_ARG, "y must not alias x");
-    hipError_t e = pda::launch_pack(x, y, B, S, H, d, unit_rms, static_cast<hipStream_t>(stream));
+    if (!std::isfinite(premul)) return fail(PDA_ERR_INVALID_ARG, "premul must be finite");
+    hipError_t e = pda::launch_pack(x, y, B, S, H, d, unit_rms, premul, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "pack launch");
     return PDA_OK;
 }

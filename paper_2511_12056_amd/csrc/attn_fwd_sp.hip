@@ -73,7 +73,10 @@ __device__ __forceinline__ void wait_vmcnt() {
     if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 }
 
-template <int NQ>
+// BASE2: the scores are already in units of log2 (the caller folded scale*log2(e) into Q), so the
+// weights are 2^(q.k) and the first sweep needs no arithmetic before the exponential at all: the
+// score accumulators start from minus the row's reference instead of from zero.
+template <int NQ, bool BASE2>
 __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnParams p) {
     constexpr int D = 128;
     constexpr int NW = 8 / NQ;            // wavefronts
@@ -197,11 +200,12 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
 
     float mc_run[NQ], l_run[NQ];     // reference max in exp2 units (max * scale * log2 e), lane's share of the running sum
     f32x16 o_acc[NQ][NDB];
+    f32x16 nref[NQ];                                   // BASE2, first sweep: minus the row's reference, as an accumulator seed
     f32x16 s_a[NQ][NKB], s_b[NQ][NKB];                 // scores of two consecutive tiles, alternating roles
     // Packed bf16 P (MFMA operand order).  One buffer serves two consecutive tiles: group (kb,u) of
     // tile t-1 is consumed by the PV MFMAs of slots 4(2kb+u)..+3, before the softmax of tile t writes it.
     unsigned p_io[NQ][NKB][2][4];
-    const float c = p.scale_log2e;   // > 0 (the host substitutes a tiny positive value for scale 0)
+    const float c = BASE2 ? 1.0f : p.scale_log2e;   // > 0 (the host substitutes a tiny positive value for scale 0)
 
     auto mask_tail = [&](f32x16 (&s)[NQ][NKB], int t) {
 #pragma unroll
@@ -287,6 +291,12 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                         m1 = fmaxf(m1, s_a[nq][(e + 1) / 16][(e + 1) % 16]);
                     }
                     mc_run[nq] = pair_max(fmaxf(m0, m1)) * c;
+                    if constexpr (BASE2) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) nref[nq][r] = -mc_run[nq];
+#pragma unroll
+                        for (int e = 0; e < 32; ++e) s_a[nq][e / 16][e % 16] -= mc_run[nq];
+                    }
                 }
             }
         }
@@ -351,7 +361,8 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                     constexpr int j = i - N_PV, kk = j / 2, kb = j % 2;
                     if constexpr (kk == 0) {
                         const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                        s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], zero, 0, 0, 0);
+                        s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk],
+                                                                              (BASE2 && !SAFE) ? nref[nq] : zero, 0, 0, 0);
                     } else {
                         s_n[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], qf[nq][kk], s_n[nq][kb], 0, 0, 0);
                     }
@@ -378,6 +389,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             auto e_lo = [](int k) constexpr { return k <= 0 ? 0 : (k >= NX ? 32 : k * 32 / NX); };
             auto fma_of = [&](auto kc, auto nq_c) {
                 constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
+                if constexpr (BASE2 && !SAFE) return;             // the MFMA output already is s - reference
                 static_for<e_lo(k), e_lo(k + 1)>([&](auto ec) {
                     constexpr int e = decltype(ec)::value;
                     float z = __builtin_fmaf(s_c[nq][e / 16][e % 16], c, -mc_new[nq]);
@@ -581,11 +593,11 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     if (c4 == 0) *lp = m + __logf(tot);
 }
 
-template <int NQ>
+template <int NQ, bool BASE2>
 static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
     constexpr int M = 256, D = 128;
-    auto kern = attn_fwd_sp_kernel<NQ>;
+    auto kern = attn_fwd_sp_kernel<NQ, BASE2>;
     static KernelSetup setup;
     int n_cu = 0;
     {
@@ -635,7 +647,7 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
 }
 
 hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, hipStream_t st) {
-    return launch_sp<1>(p, BH, st);
+    return p.base2 ? launch_sp<1, true>(p, BH, st) : launch_sp<1, false>(p, BH, st);
 }
 
 }  // namespace pda

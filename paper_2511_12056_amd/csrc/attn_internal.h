@@ -58,6 +58,7 @@ struct AttnParams {
     int64_t part_keys;
     float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
     float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
+    int base2;              // scores are already in log2 units: weights 2^(q.k), scale_log2e == 1
     int redo_always;        // software-pipelined kernel: sweep every item a second time with the running max (testing aid)
 };
 
@@ -99,8 +100,9 @@ hipError_t launch_postprocess(const PostParams& p, hipStream_t st);
 hipError_t launch_scatter_heads(const float* src, float* dst, int64_t S, int d, int hg, int H, int h0,
                                 int h, int n, int arrival, hipStream_t st);
 
-// Token-major fp32 [B,S,H,d] -> head-major bf16 [B,H,S,d] (d = 64 or 128), optional unit-RMS vectors.
-hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, hipStream_t st);
+// Token-major fp32 [B,S,H,d] -> head-major bf16 [B,H,S,d] (d = 64 or 128), optional unit-RMS vectors,
+// every element times premul before the rounding.
+hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, float premul, hipStream_t st);
 
 // MFMA-only loop (probe.hip): n_cu workgroups x 8 wavefronts, each wavefront issues 8*iters MFMAs
 // (32x32x16 bf16) on fragments read from src (n_frag 16-byte fragments); sink: >= 512 floats.

@@ -74,7 +74,7 @@ hipError_t launch_scatter_heads(const float* src, float* dst, int64_t S, int d, 
 // writes are contiguous and the fp32 reads are d-float segments H*d floats apart.
 template <int LPV>
 __global__ __launch_bounds__(256) void pack_heads_kernel(const float4* __restrict__ x, uint2* __restrict__ y,
-                                                         int64_t S, int H, int64_t n_vec /* B*H*S */, int unit_rms) {
+                                                         int64_t S, int H, int64_t n_vec /* B*H*S */, int unit_rms, float premul) {
     constexpr int VPB = 256 / LPV;                            // vectors per workgroup pass
     const int lane = threadIdx.x % LPV;
     const int64_t n_pass = (n_vec + VPB - 1) / VPB;
@@ -93,8 +93,10 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const float4* __restric
             float ss = a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
 #pragma unroll
             for (int m = 1; m < LPV; m <<= 1) ss += __shfl_xor(ss, m, LPV);
-            const float inv = ss > 0.f ? 1.0f / sqrtf(ss * (1.0f / (4 * LPV))) : 0.f;
+            const float inv = ss > 0.f ? premul / sqrtf(ss * (1.0f / (4 * LPV))) : 0.f;
             a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+        } else if (premul != 1.0f) {
+            a.x *= premul; a.y *= premul; a.z *= premul; a.w *= premul;
         }
         if (live) {
             y[o * LPV + lane] = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));   // round to nearest even
@@ -102,14 +104,14 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const float4* __restric
     }
 }
 
-hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, hipStream_t st) {
+hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, float premul, hipStream_t st) {
     const int64_t n_vec = (int64_t)B * H * S;
     const float4* xs = reinterpret_cast<const float4*>(x);
     uint2* yd = reinterpret_cast<uint2*>(y);
     if (d == 128) {
-        hipLaunchKernelGGL(pack_heads_kernel<32>, dim3(grid_1d(n_vec * 32)), dim3(256), 0, st, xs, yd, S, H, n_vec, unit_rms);
+        hipLaunchKernelGGL(pack_heads_kernel<32>, dim3(grid_1d(n_vec * 32)), dim3(256), 0, st, xs, yd, S, H, n_vec, unit_rms, premul);
     } else {
-        hipLaunchKernelGGL(pack_heads_kernel<16>, dim3(grid_1d(n_vec * 16)), dim3(256), 0, st, xs, yd, S, H, n_vec, unit_rms);
+        hipLaunchKernelGGL(pack_heads_kernel<16>, dim3(grid_1d(n_vec * 16)), dim3(256), 0, st, xs, yd, S, H, n_vec, unit_rms, premul);
     }
     return hipGetLastError();
 }

@@ -18,12 +18,12 @@ def pda():
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "pipedit_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pda_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(pda_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
-    assert names == ["pda_attn_fwd", "pda_attn_fwd_strided", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
+    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_strided", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
                      "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_mfma_rate", "pda_version"]
     lib = C.CDLL(pda.lib_path())
@@ -126,12 +126,18 @@ def test_postprocess_rejects_bad_arguments(pda):
 
 def test_pack_rejects_bad_arguments(pda):
     f = pda.lib.pda_pack_heads
-    assert f(64, 128, 1, 8, 2, 32, 1, None) == 2 and "head dim" in pda.last_error()
-    assert f(64, 128, -1, 8, 2, 64, 1, None) == 1
-    assert f(None, 128, 1, 8, 2, 64, 1, None) == 1
-    assert f(64, 72, 1, 8, 2, 64, 1, None) == 2
-    assert f(64, 64, 1, 8, 2, 64, 1, None) == 1 and "alias" in pda.last_error()
-    assert f(None, None, 1, 0, 2, 64, 1, None) == 0
+    assert f(64, 128, 1, 8, 2, 32, 1, 1.0, None) == 2 and "head dim" in pda.last_error()
+    assert f(64, 128, -1, 8, 2, 64, 1, 1.0, None) == 1
+    assert f(None, 128, 1, 8, 2, 64, 1, 1.0, None) == 1
+    assert f(64, 72, 1, 8, 2, 64, 1, 1.0, None) == 2
+    assert f(64, 64, 1, 8, 2, 64, 1, 1.0, None) == 1 and "alias" in pda.last_error()
+    assert f(64, 128, 1, 8, 2, 64, 1, float("inf"), None) == 1 and "premul" in pda.last_error()
+    assert f(None, None, 1, 0, 2, 64, 1, 1.0, None) == 0
+    g = pda.lib.pda_attn_fwd_base2
+    assert g(128, 128, 128, 128, 128, 1, 1, 8, 8, 32, 8, None) == 2
+    assert g(128, 128, 128, 128, 128, 1, 1, 8, 8, 64, 9, None) == 1
+    assert g(None, 128, 128, 128, 128, 1, 1, 8, 8, 64, 8, None) == 1
+    assert g(None, None, None, None, None, 1, 1, 0, 8, 64, 8, None) == 0
 
 
 def test_planner_rejects_bad_arguments(pda):

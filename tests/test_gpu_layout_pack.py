@@ -198,3 +198,74 @@ def test_mfma_rate_probe_runs():
     assert ms > 0 and 100.0 < tf < 2600.0, (tf, ms)          # between a tenth of and the nominal bf16 peak
     tz, _ = pda.probe_mfma_rate(torch.zeros_like(x), 1 << 14)
     assert 100.0 < tz < 2600.0
+
+
+@pytest.mark.parametrize("B,H,S,Skv,d,n_v", [(1, 2, 515, 1100, 128, 1050), (2, 3, 300, 4200, 128, 4200), (1, 2, 200, 333, 64, 300),
+                                             (1, 5, 300, 2500, 128, 2500)])
+def test_base2_attention_matches_oracle(B, H, S, Skv, d, n_v):
+    """Scores taken as exponents of 2 == the oracle with scale = ln 2."""
+    import math
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    qb, kb, vb = gen_qkv(700 + H, B, H, S, Skv, d, unit_rms=True)
+    # bring the scores into a sensible range for exponents of 2: Q times scale*log2(e), rounded to bf16
+    c = d ** -0.5 * math.log2(math.e)
+    qb = f32_to_bf16_bits(bf16_bits_to_f32(qb) * np.float32(c))
+    out = torch.full((B, H, S, d), float("nan"), device="cuda"); lse = torch.full((B, H, S), float("nan"), device="cuda")
+    pda.attn_fwd_base2(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out, lse, n_v)
+    torch.cuda.synchronize()
+    ro, rl = attention(qb, kb, vb, math.log(2.0), n_v)
+    assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, "base2")
+    # the general entry point with scale = ln 2 computes the same function
+    out2 = torch.empty_like(out); lse2 = torch.empty_like(lse)
+    pda.attn_fwd(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out2, lse2, math.log(2.0), n_v)
+    torch.cuda.synchronize()
+    assert ((out - out2).norm() / out2.norm()).item() < 5e-3
+    assert ((lse - lse2).abs() / lse2.abs().clamp(min=1)).max().item() < 1e-5
+
+
+def test_base2_overflow_redo():
+    import math
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    rng = np.random.default_rng(78)
+    B, H, Sq, Skv, d = 1, 2, 300, 900, 128
+    q = rng.standard_normal((B, H, Sq, d)).astype(np.float32)
+    k = (rng.standard_normal((B, H, Skv, d)) * 0.01).astype(np.float32)
+    v = rng.standard_normal((B, H, Skv, d)).astype(np.float32)
+    k[:, 0, 200:] *= 2000.0
+    qb, kb, vb = f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v)
+    out = torch.full((B, H, Sq, d), float("nan"), device="cuda"); lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+    pda.attn_fwd_base2(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out, lse)
+    torch.cuda.synchronize()
+    ro, rl = attention(qb, kb, vb, math.log(2.0), Skv)
+    assert np.abs(rl).max() > 200
+    assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, "base2 overflow redo")
+
+
+def test_pack_with_folded_scale_feeds_base2_attention():
+    """Q packed with premul = scale*log2(e) + base-2 attention against the oracle on the oracle's
+    own pack (same premul, one rounding) with scale ln 2."""
+    import math
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention_head
+    from oracle.pack import pack_heads
+    B, S, H, d = 1, 700, 2, 128
+    c = d ** -0.5 * math.log2(math.e)
+    xs = [_rand((B, S, H, d), 40 + i) for i in range(3)]
+    dev = []
+    for i, x in enumerate(xs):
+        y = torch.empty(B, H, S, d, dtype=torch.bfloat16, device="cuda")
+        pda.pack_heads(torch.from_numpy(x).cuda(), y, unit_rms=True, premul=c if i == 0 else 1.0)
+        dev.append(y)
+    out = torch.empty(B, H, S, d, device="cuda"); lse = torch.empty(B, H, S, device="cuda")
+    pda.attn_fwd_base2(dev[0], dev[1], dev[2], out, lse)
+    torch.cuda.synchronize()
+    qo = pack_heads(xs[0], True, premul=c)
+    ko, vo = pack_heads(xs[1], True), pack_heads(xs[2], True)
+    for hh in range(H):
+        ro, rl = attention_head(qo[0, hh], ko[0, hh], vo[0, hh], math.log(2.0), S)
+        assert_close(out[0, hh].cpu().numpy(), lse[0, hh].cpu().numpy(), ro, rl, f"folded scale head {hh}")

@@ -47,3 +47,15 @@ def test_zero_vector_stays_zero():
     x[0, 1, 1] = 3.0
     y = K.pack_heads(x, True)
     assert np.all(y[0, :, 0] == 0) and np.all(y[0, 0, 1] == 0) and np.all(y[0, 1, 1] == 1.0)
+
+
+def test_premul_is_applied_before_the_single_rounding():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((1, 16, 2, 64))
+    c = 0.1275174
+    y = K.pack_heads(x, True, premul=c)
+    exact = x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True)) * c
+    assert np.array_equal(y, K.round_to_bf16(exact.transpose(0, 2, 1, 3)))
+    assert np.array_equal(K.pack_heads(x, False, premul=0.5), 0.5 * K.pack_heads(x, False))     # power of two: exact
+    # not the same as rounding first and scaling afterwards
+    assert not np.array_equal(y, K.round_to_bf16(K.pack_heads(x, True) * c))
