@@ -41,6 +41,21 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
     return __builtin_bit_cast(unsigned, h);
 }
 
+// Streaming (non-temporal) 16- and 8-byte accesses for data that is touched once: they leave the
+// caches to data that is reused and measurably raise the rate of the HBM-bound kernels.
+__device__ __forceinline__ float4 nt_load4(const float4* p) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float4* p, const float4& a) {
+    const f32x4 v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+__device__ __forceinline__ void nt_store2(uint2* p, unsigned lo, unsigned hi) {
+    const u32x2 v = {lo, hi};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
+}
+
 // Compile-time loop: f(std::integral_constant<int, I>) for I in [I0, N).
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void postprocess_kernel(const PostParams p) {
         const int rem = (int)(t - r * per_row);
         const int i = rem / p.D4;
         const int c = rem - i * p.D4;
-        dst[r * out_row + (int64_t)(i * p.h + j) * p.D4 + c] = src[r * p.row_stride4 + rem];
+        nt_store4(dst + r * out_row + (int64_t)(i * p.h + j) * p.D4 + c, nt_load4(src + r * p.row_stride4 + rem));
     }
 }
 
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void scatter_heads_kernel(const float4* __rest
         const int c = (int)(rem - s * d4);
         const int k = h0 + jj;                               // global head = i*h + j
         const int slot = arrival ? (k % h) * n + k / h : k;  // k_mod(i,j) = j*n + i, or k_orig
-        dst[(s * H + slot) * d4 + c] = src[t];
+        nt_store4(dst + (s * H + slot) * d4 + c, nt_load4(src + t));
     }
 }
 
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const float4* __restric
             const int64_t s = o - bh * S;
             const int64_t b = bh / H;
             const int hh = (int)(bh - b * H);
-            a = x[((b * S + s) * H + hh) * LPV + lane];
+            a = nt_load4(x + ((b * S + s) * H + hh) * LPV + lane);
         }
         if (unit_rms) {
             float ss = a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const float4* __restric
             a.x *= premul; a.y *= premul; a.z *= premul; a.w *= premul;
         }
         if (live) {
-            y[o * LPV + lane] = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));   // round to nearest even
+            nt_store2(y + o * LPV + lane, pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));   // round to nearest even
         }
     }
 }

@@ -5,6 +5,7 @@
 // cache line broadcast); the first of them also writes the merged lse.
 #include <hip/hip_runtime.h>
 #include "attn_internal.h"
+#include "attn_device.h"
 
 namespace pda {
 
@@ -30,14 +31,14 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeParams p, int dq 
             if (j < n) {
                 const float w = __expf(l[j] - msafe);      // exp(-inf) = 0 for an empty partial
                 if (w > 0.f) {                             // a weight-0 partial is never read
-                    const float4 x = reinterpret_cast<const float4*>(p.part[j])[i];
+                    const float4 x = nt_load4(reinterpret_cast<const float4*>(p.part[j]) + i);
                     acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
                     tot += w;
                 }
             }
         const float inv = tot > 0.f ? 1.0f / tot : 0.f;
         acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-        reinterpret_cast<float4*>(p.out)[i] = acc;
+        nt_store4(reinterpret_cast<float4*>(p.out) + i, acc);
         if (p.lse_out != nullptr && i - row * dq == 0)
             p.lse_out[row] = tot > 0.f ? msafe + __logf(tot) : -INFINITY;
     }
@@ -45,7 +46,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeParams p, int dq 
 
 __global__ __launch_bounds__(256) void copy_f32_kernel(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n4) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
-        dst[i] = src[i];
+        nt_store4(dst + i, nt_load4(src + i));
 }
 
 static unsigned grid_for(int64_t items) {
