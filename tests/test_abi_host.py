@@ -182,3 +182,14 @@ def test_attn_fwd_strided_rejects_bad_arguments(pda):
     assert call(good[:4] + [1024, 1024] + good[6:]) == 1 and "batch stride" in pda.last_error()
     assert call([-8] + good[1:]) == 1
     assert call(good, shape=[128, 128, 128, 128, 128, 2, 2, 0, 8, 64]) == 0      # empty: no-op
+
+
+def test_header_is_plain_c(tmp_path):
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "pipedit_attn.h"\nint main(void) { return PDA_MAX_PARTIALS == 16 ? 0 : 1; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
