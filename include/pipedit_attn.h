@@ -91,6 +91,15 @@ int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out
                          float scale, int64_t kv_valid_len, int64_t q_offset, void* stream);
 
 /*
+ * pda_attn_fwd with a bf16 output, for results that go straight on to the next projection and not
+ * through pda_attn_merge (which takes fp32 partials): out is [B,H,Sq,d] bf16, rounded to nearest
+ * even from the fp32 result; lse stays fp32.  d must be 128.  Everything else as pda_attn_fwd.
+ */
+int pda_attn_fwd_bf16out(const void* q, const void* k, const void* v, void* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, void* stream);
+
+/*
  * pda_attn_fwd for callers that fold the softmax scale into Q where Q is produced (for instance
  * pda_pack_heads with premul = scale * log2(e), which costs no extra rounding there): the scores
  * s_j = <q_i, k_j> are taken to be in units of log2, i.e.

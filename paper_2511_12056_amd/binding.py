@@ -50,6 +50,8 @@ def _load() -> C.CDLL:
     lib.pda_pipesp_postprocess.argtypes = [C.POINTER(vp), i32, i32, i64, fp, i64, i32, vp]
     lib.pda_pipesp_postprocess.restype = i32
     lib.pda_pack_heads.argtypes = [fp, vp, i32, i64, i32, i32, i32, f32, vp]
+    lib.pda_attn_fwd_bf16out.argtypes = [vp, vp, vp, vp, fp, i32, i32, i64, i64, i32, f32, i64, vp]
+    lib.pda_attn_fwd_bf16out.restype = i32
     lib.pda_attn_fwd_base2.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, i64, vp]
     lib.pda_attn_fwd_base2.restype = i32
     lib.pda_pack_heads.restype = i32
@@ -119,6 +121,22 @@ def attn_fwd(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None
     n_v = Skv if kv_valid_len is None else int(kv_valid_len)
     _check(lib.pda_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
                             n_v, int(q_offset), _stream_handle(stream)))
+    return out, lse
+
+
+def attn_fwd_bf16out(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None, stream=None):
+    """pda_attn_fwd_bf16out: as attn_fwd with out [B,H,Sq,d] in bf16 (d = 128)."""
+    import torch
+    B, H, Sq, d = q.shape
+    Skv = k.shape[2]
+    _expect(q, torch.bfloat16, (B, H, Sq, d), "q")
+    _expect(k, torch.bfloat16, (B, H, Skv, d), "k")
+    _expect(v, torch.bfloat16, (B, H, Skv, d), "v")
+    _expect(out, torch.bfloat16, (B, H, Sq, d), "out")
+    _expect(lse, torch.float32, (B, H, Sq), "lse")
+    n_v = Skv if kv_valid_len is None else int(kv_valid_len)
+    _check(lib.pda_attn_fwd_bf16out(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
+                                    n_v, _stream_handle(stream)))
     return out, lse
 
 

@@ -73,7 +73,7 @@ Strides compact_strides(int H, int64_t Sq, int64_t Skv, int d) {
 // base2: the scores q.k are already in log2 units (scale is then ln 2 and is not applied again).
 hipError_t launch_strided(const void* q, const void* k, const void* v, float* out, float* lse,
                           int B, int hg, int64_t Sq, int d, const Strides& s, float scale, int64_t n_v, hipStream_t st,
-                          bool base2 = false) {
+                          bool base2 = false, bool out_bf16 = false) {
     pda::AttnParams p{};
     p.q = static_cast<const __bf16*>(q);
     p.k = static_cast<const __bf16*>(k);
@@ -91,6 +91,7 @@ hipError_t launch_strided(const void* q, const void* k, const void* v, float* ou
     // scale 0 is run with a tiny positive factor so that hidden keys (-inf scores) still get exp2(-inf) = 0
     p.scale_log2e = base2 ? 1.0f : std::fmax(scale * 1.4426950408889634f, 1e-37f);
     p.base2 = base2 ? 1 : 0;
+    p.out_bf16 = out_bf16 ? 1 : 0;
     return pda::launch_attn_fwd(p, B * hg, d, attn_variant(), st);
 }
 
@@ -234,6 +235,19 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
     hipError_t e = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H,
                                 static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "attention launch");
+    return PDA_OK;
+}
+
+int pda_attn_fwd_bf16out(const void* q, const void* k, const void* v, void* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, void* stream) {
+    int rc = check_attn_args(q, k, v, static_cast<const float*>(out), lse, B, H, Sq, Skv, d, scale, kv_valid_len);
+    if (rc != PDA_OK) return rc;
+    if (d != 128) return fail(PDA_ERR_UNSUPPORTED, "a bf16 output needs d = 128 (got %d)", d);
+    if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
+    hipError_t e = launch_strided(q, k, v, static_cast<float*>(out), lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d),
+                                  scale, kv_valid_len, static_cast<hipStream_t>(stream), false, true);
     if (e != hipSuccess) return hip_fail(e, "attention launch");
     return PDA_OK;
 }

@@ -285,10 +285,12 @@ __global__ void attn_empty_kernel(const AttnParams p, int D) {
     const int bh = blockIdx.y;
     const int b = bh / p.Hg, h = bh - b * p.Hg;
     float* op = p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs;
+    __bf16* oph = reinterpret_cast<__bf16*>(p.out) + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs;
     float* lp = p.lse + (int64_t)b * p.l_bs + (int64_t)h * p.l_hs;
     const int64_t n = p.Sq * D;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        op[i] = 0.f;
+        if (p.out_bf16) oph[i] = (__bf16)0.f;
+        else op[i] = 0.f;
         if (i < p.Sq) lp[i] = -INFINITY;
     }
 }
@@ -313,6 +315,7 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipS
         return hipGetLastError();
     }
     if (D == 64) return launch_variant<64, 1, 4, 64, 2>(p, BH, st);
+    if (p.out_bf16 && variant != 3) variant = 0;                       // only the software-pipelined kernel writes bf16
     switch (variant) {
         case 1:  return launch_variant<128, 1, 4, 64, 2>(p, BH, st);   // reference tiling, M=128, two workgroups per CU
         case 2:  return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // reference tiling, M=256, two waves per SIMD

@@ -119,16 +119,22 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     float* __restrict__ op;
     float* __restrict__ lp;
     int64_t row_sub;                                   // subtracted from the global row on store
-    if (part == 0) {
-        op = p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs;
+    // With a bf16 `out` the merge pass needs fp32 partials of ALL parts of a cut tile, part 0 included.
+    const bool cut = p.split > 1 && tile >= p.n_full;
+    const bool to_ws = part > 0 || (cut && p.out_bf16);
+    if (!to_ws) {
+        op = p.out + (p.out_bf16 ? 0 : (int64_t)b * p.o_bs + (int64_t)h * p.o_hs);
         lp = p.lse + (int64_t)b * p.l_bs + (int64_t)h * p.l_hs;
         row_sub = 0;
     } else {
-        const int64_t slot = (int64_t)(tile - p.n_full) * (p.split - 1) + (part - 1);
+        const int64_t slot = p.out_bf16 ? (int64_t)(tile - p.n_full) * p.split + part
+                                        : (int64_t)(tile - p.n_full) * (p.split - 1) + (part - 1);
         op = p.part_out + slot * (M * D);
         lp = p.part_lse + slot * M;
         row_sub = (int64_t)q_tile * M;
     }
+    __bf16* __restrict__ oph = reinterpret_cast<__bf16*>(p.out) + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs;
+    const bool store_bf16 = p.out_bf16 && !to_ws;
 
     const int64_t Sq = p.Sq;
     const int n_v = (int)(kv1 - kv0);                 // keys of this item, >= 1
@@ -547,7 +553,12 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                 for (int a = 0; a < 4; ++a) {
                     f32x4 o4 = {o_acc[nq][db][4 * a] * inv, o_acc[nq][db][4 * a + 1] * inv,
                                 o_acc[nq][db][4 * a + 2] * inv, o_acc[nq][db][4 * a + 3] * inv};
-                    *reinterpret_cast<f32x4*>(op + (row - row_sub) * D + db * 32 + a * 8 + 4 * lh) = o4;
+                    if (store_bf16) {
+                        const u32x2 h2 = {pack_bf16(o4[0], o4[1]), pack_bf16(o4[2], o4[3])};
+                        *reinterpret_cast<u32x2*>(oph + row * D + db * 32 + a * 8 + 4 * lh) = h2;
+                    } else {
+                        *reinterpret_cast<f32x4*>(op + (row - row_sub) * D + db * 32 + a * 8 + 4 * lh) = o4;
+                    }
                 }
             if (lh == 0) lp[row - row_sub] = mc_run[nq] * 0.6931471805599453f + __logf(l_tot);
         }
@@ -567,29 +578,39 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     const int b = bh / p.Hg, h = bh - b * p.Hg;
     const int64_t row = (int64_t)q_tile * M + r_in;
     if (row >= p.Sq) return;
-    float* op = p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D;
     float* lp = p.lse + (int64_t)b * p.l_bs + (int64_t)h * p.l_hs + row;
+    // fp32 out: part 0 sits in out/lse and parts 1.. in the workspace; bf16 out: all parts in the workspace
+    const int n_ws = p.out_bf16 ? p.split : p.split - 1;
+    const int64_t slot0 = (int64_t)(tile - p.n_full) * n_ws;
     float l[4];
-    l[0] = *lp;
-    float m = l[0];
-    for (int j = 1; j < p.split; ++j) {
-        const int64_t slot = (int64_t)(tile - p.n_full) * (p.split - 1) + (j - 1);
-        l[j] = p.part_lse[slot * M + r_in];
+    float4 x[4];
+    float m = -INFINITY;
+    for (int j = 0; j < p.split; ++j) {
+        if (j == 0 && !p.out_bf16) {
+            l[0] = *lp;
+            x[0] = reinterpret_cast<const float4*>(p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D)[c4];
+        } else {
+            const int64_t slot = slot0 + (p.out_bf16 ? j : j - 1);
+            l[j] = p.part_lse[slot * M + r_in];
+            x[j] = reinterpret_cast<const float4*>(p.part_out + (slot * M + r_in) * D)[c4];
+        }
         m = fmaxf(m, l[j]);
     }
-    float4 acc = reinterpret_cast<const float4*>(op)[c4];
-    float w = __expf(l[0] - m), tot = w;
-    acc.x *= w; acc.y *= w; acc.z *= w; acc.w *= w;
-    for (int j = 1; j < p.split; ++j) {
-        const int64_t slot = (int64_t)(tile - p.n_full) * (p.split - 1) + (j - 1);
-        const float4 x = reinterpret_cast<const float4*>(p.part_out + (slot * M + r_in) * D)[c4];
-        w = __expf(l[j] - m);
-        acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float tot = 0.f;
+    for (int j = 0; j < p.split; ++j) {
+        const float w = __expf(l[j] - m);
+        acc.x += w * x[j].x; acc.y += w * x[j].y; acc.z += w * x[j].z; acc.w += w * x[j].w;
         tot += w;
     }
     const float inv = 1.0f / tot;
     acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-    reinterpret_cast<float4*>(op)[c4] = acc;
+    if (p.out_bf16) {
+        __bf16* oh = reinterpret_cast<__bf16*>(p.out) + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D;
+        reinterpret_cast<uint2*>(oh)[c4] = make_uint2(pack_bf16(acc.x, acc.y), pack_bf16(acc.z, acc.w));
+    } else {
+        reinterpret_cast<float4*>(p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D)[c4] = acc;
+    }
     if (c4 == 0) *lp = m + __logf(tot);
 }
 
@@ -631,7 +652,7 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
     if (split > 1) {
         p.n_full = (int)(n_tiles - n_cut);
         p.part_keys = ((p.n_v + split - 1) / split + 63) / 64 * 64;
-        const size_t slots = (size_t)n_cut * (split - 1);
+        const size_t slots = (size_t)n_cut * (p.out_bf16 ? split : split - 1);
         float* ws = nullptr;
         hipError_t e = attn_workspace(st, slots * (M * D + M) * sizeof(float), &ws);
         if (e != hipSuccess) return e;

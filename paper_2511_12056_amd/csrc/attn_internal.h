@@ -58,6 +58,7 @@ struct AttnParams {
     int64_t part_keys;
     float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
     float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
+    int out_bf16;           // software-pipelined kernel: `out` points to bf16 elements (same element strides)
     int base2;              // scores are already in log2 units: weights 2^(q.k), scale_log2e == 1
     int redo_always;        // software-pipelined kernel: sweep every item a second time with the running max (testing aid)
 };

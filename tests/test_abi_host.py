@@ -23,7 +23,7 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
-    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_strided", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
+    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_bf16out", "pda_attn_fwd_strided", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
                      "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_mfma_rate", "pda_version"]
     lib = C.CDLL(pda.lib_path())
@@ -193,3 +193,11 @@ def test_header_is_plain_c(tmp_path):
     src.write_text('#include "pipedit_attn.h"\nint main(void) { return PDA_MAX_PARTIALS == 16 ? 0 : 1; }\n')
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
                     "-I", os.path.join(ROOT, "include"), str(src)], check=True)
+
+
+def test_bf16out_rejects_bad_arguments(pda):
+    f = pda.lib.pda_attn_fwd_bf16out
+    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 64, 1.0, 8, None) == 2 and "d = 128" in pda.last_error()
+    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 9, None) == 1
+    assert f(128, 128, 128, None, 128, 1, 1, 8, 8, 128, 1.0, 8, None) == 1
+    assert f(None, None, None, None, None, 0, 1, 8, 8, 128, 1.0, 8, None) == 0

@@ -238,3 +238,23 @@ np.savez(sys.argv[2], **res)
         got = np.load(f)
         for i, (ro, rl) in enumerate(refs):
             assert_close(got[f"o{i}"], got[f"l{i}"], ro, rl, f"variant {variant} shape {i}")
+
+
+@pytest.mark.parametrize("B,H,Sq,Skv,n_v", [(1, 2, 515, 1100, 1050), (2, 5, 300, 2500, 2500), (1, 3, 5000, 5000, 4990),
+                                            (1, 1, 77, 64, 0), (1, 24, 700, 3000, 3000)])
+def test_bf16_output_is_the_rounded_fp32_output(B, H, Sq, Skv, n_v):
+    """Same kernels, same arithmetic; only the last store differs (tiles cut into key ranges are
+    merged from fp32 partials in both cases).  Hence bit equality with the rounded fp32 result, and
+    through it parity with the oracle."""
+    import torch
+    import paper_2511_12056_amd as pda
+    d = 128
+    qb, kb, vb = gen_qkv(300 + H, B, H, Sq, Skv, d, unit_rms=True)
+    q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+    o32 = torch.full((B, H, Sq, d), float("nan"), device="cuda"); l32 = torch.full((B, H, Sq), float("nan"), device="cuda")
+    o16 = torch.full((B, H, Sq, d), float("nan"), device="cuda", dtype=torch.bfloat16); l16 = torch.full_like(l32, float("nan"))
+    pda.attn_fwd(q, k, v, o32, l32, d ** -0.5, n_v)
+    pda.attn_fwd_bf16out(q, k, v, o16, l16, d ** -0.5, n_v)
+    torch.cuda.synchronize()
+    assert torch.equal(o16, o32.to(torch.bfloat16))
+    assert torch.equal(l16, l32)
