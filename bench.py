@@ -155,7 +155,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the measurements of the steps next to the attention call")
     ap.add_argument("--t-linear-ms", type=float, default=None, help="time of the linear projections for the planner example")
@@ -248,7 +248,8 @@ def main():
                            "frac": merge_bytes / (merge_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS,
                            "launch_ms": merge_ms, "bytes_per_launch": merge_bytes,
                            "traffic": measured_traffic("merge_kernel_4")},
-        "pipeline": {"group_ms_mean": launch_ms, "total_ms_mean": sum(total_ms_all) / len(total_ms_all),
+        "pipeline": {"group_ms_mean": launch_ms, "group_ms_median": sorted(group_ms_all)[len(group_ms_all) // 2],
+                     "group_ms_min": min(group_ms_all), "total_ms_mean": sum(total_ms_all) / len(total_ms_all),
                      "sum_group_ms_mean": sum(group_ms_all) / args.steps, "split_pass_ms": split_ms,
                      "chunked_tflops": flops_chunked / (sum(total_ms_all) / len(total_ms_all) * 1e-3) * 1e-12},
     }
