@@ -61,6 +61,55 @@ def cpu_baseline(w, qb, kb, vb, target_s=15.0):
             "full_problem_extrapolated_s": w.flops / (flops / dt)}
 
 
+class ClockSampler:
+    """Best effort: samples the shader clock the driver reports (sysfs pp_dpm_sclk, the starred
+    level) from a host thread while a region runs; empty if the file is not readable."""
+
+    def __init__(self, period_s=0.02):
+        import glob
+        import threading
+        files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.path = files[0] if files else None
+        self.period = period_s
+        self.samples = []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _read(self):
+        try:
+            with open(self.path) as f:
+                for line in f:
+                    if "*" in line:
+                        return int("".join(ch for ch in line.split(":")[1] if ch.isdigit()))
+        except (OSError, ValueError, IndexError, TypeError):
+            return None
+        return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            v = self._read()
+            if v is not None:
+                self.samples.append(v)
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        if self.path:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self.path:
+            self._thread.join(timeout=1.0)
+
+    def summary(self):
+        if not self.samples:
+            return None
+        x = sorted(self.samples)
+        return {"min": x[0], "median": x[len(x) // 2], "max": x[-1], "samples": len(x),
+                "source": "sysfs pp_dpm_sclk sampled from the host during the timed steps"}
+
+
 def _event_ms(torch, stream, fn, iters=5):
     """Mean duration of fn() (which enqueues on `stream`) over `iters` calls, by events on that stream."""
     fn()
@@ -210,11 +259,12 @@ def main():
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, True)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    with ClockSampler() as clocks:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
 
     flops_chunked = float(w.flops)
     flops_split = 2.0 * 4.0 * w.Sq * w.Skv * w.d * H5          # query-range pass + key-chunk pass
@@ -253,6 +303,7 @@ def main():
                      "sum_group_ms_mean": sum(group_ms_all) / args.steps, "split_pass_ms": split_ms,
                      "chunked_tflops": flops_chunked / (sum(total_ms_all) / len(total_ms_all) * 1e-3) * 1e-12},
     }
+    res["roofline"]["sclk_mhz"] = clocks.summary()
     # context for the clock the chip sustains on this data: an MFMA-only loop fed with Q's values
     probe_tf, probe_ms = pda.probe_mfma_rate(q, 1 << 20, stream=cs)
     res["roofline"]["mfma_only_same_data"] = {"achieved": probe_tf, "unit": "TFLOP/s", "ms": probe_ms,
