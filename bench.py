@@ -123,6 +123,74 @@ def _event_ms(torch, stream, fn, iters=5):
     return a.elapsed_time(b) / iters
 
 
+def _errors(out_gpu, lse_gpu, out_ref, lse_ref):
+    """The error measures of the parity gates, against fp64 oracle rows."""
+    import numpy as np
+    diff = out_gpu.astype(np.float64) - out_ref
+    return {"max_abs": float(np.abs(diff).max()), "mean_abs": float(np.abs(diff).mean()),
+            "rel_l2": float(np.sqrt((diff ** 2).sum() / max((out_ref ** 2).sum(), 1e-300))),
+            "lse_rel": float((np.abs(lse_gpu.astype(np.float64) - lse_ref) / np.maximum(np.abs(lse_ref), 1.0)).max())}
+
+
+def _timed_launches(torch, stream, fn, iters):
+    """Durations (ms) of `iters` single calls of fn() on `stream`, one event pair per call."""
+    fn(); fn(); fn()
+    stream.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in ev:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    stream.synchronize()
+    return sorted(a.elapsed_time(b) for a, b in ev)
+
+
+def measure_config(pda, torch, idx, cs, tensors=None, oracle_rows=192):
+    """One workload of the benchmark spec through pda_attn_fwd: median / min launch time over its own
+    iteration count, TFLOP/s with the nominal key count, fraction of the bf16 peak, and the parity
+    errors of that launch against the fp64 oracle (C1: every row; others: a seeded row sample of the
+    first and last head against all keys).  C4 is one 3-head group of its pipeline, C5 its unsplit
+    6-head pass (the split passes are part of the timed step and of the GPU tests)."""
+    import numpy as np
+    from oracle import attention_head
+    from synth import CONFIGS, gen_qkv_parallel, to_dev_bf16
+    w = CONFIGS[idx]
+    H = w.heads_per_group if idx == 4 else w.H
+    if tensors is None:
+        qb, kb, vb = gen_qkv_parallel(w, heads=(0, H), workers=min(16, os.cpu_count() or 8))
+        q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+    else:
+        (qb, kb, vb), (q, k, v) = tensors
+        qb, kb, vb = qb[:, :H], kb[:, :H], vb[:, :H]
+        q, k, v = q[:, :H].contiguous(), k[:, :H].contiguous(), v[:, :H].contiguous()
+    out = torch.empty(w.B, H, w.Sq, w.d, device="cuda")
+    lse = torch.empty(w.B, H, w.Sq, device="cuda")
+    n_v = w.kv_valid_len
+    iters = {1: 200, 2: 50, 3: 10, 4: 8, 5: 5}[idx]
+    with torch.cuda.stream(cs):
+        ms = _timed_launches(torch, cs, lambda: pda.attn_fwd(q, k, v, out, lse, w.scale, n_v, stream=cs), iters)
+    med, mn = ms[len(ms) // 2], ms[0]
+    flops = 4.0 * w.Sq * w.Skv * w.d * H * w.B
+    res = {"workload": w.name, "launch": f"pda_attn_fwd B={w.B} H={H} Sq={w.Sq} Skv={w.Skv} d={w.d} kv_valid_len={n_v}",
+           "iters": iters, "median_ms": med, "min_ms": mn, "tflops": flops / (med * 1e-3) * 1e-12,
+           "frac_of_bf16_peak": flops / (med * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS,
+           "plan": pda.attn_tail_plan(w.B, H, w.Sq, n_v, w.d)}
+    if idx == 1:
+        res["note"] = "cache resident and launch bound: 0.54 GFLOP per launch"
+    o, l = out.cpu().numpy(), lse.cpu().numpy()
+    errs = {}
+    for h in sorted({0, H - 1}):
+        rng = np.random.default_rng(w.seed + h)
+        rows = np.arange(w.Sq) if idx == 1 else np.unique(np.concatenate(
+            [[0, w.Sq - 1, 255, 256], rng.choice(w.Sq, size=oracle_rows, replace=False)]))
+        ro, rl = attention_head(qb[0, h], kb[0, h], vb[0, h], w.scale, n_v, rows=rows)
+        errs[f"head{h}"] = _errors(o[0, h][rows], l[0, h][rows], ro, rl)
+    res["parity_vs_oracle"] = {key: max(e[key] for e in errs.values()) for key in ("max_abs", "mean_abs", "rel_l2", "lse_rel")}
+    res["parity_rows_per_head"] = int(len(rows))
+    return res
+
+
+
 def next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, t_linear_ms):
     """The steps next to the attention call at the same 720p shape, outside the timed step:
     post-processing, token-major hand-off, pack, unequal vs padded head groups, planner."""
@@ -208,14 +276,28 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the measurements of the steps next to the attention call")
     ap.add_argument("--t-linear-ms", type=float, default=None, help="time of the linear projections for the planner example")
+    ap.add_argument("--config", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
+                    help="measure only workload N of BASELINE.json through pda_attn_fwd and print its JSON line "
+                         "(0, the default: the headline step, with every workload in the all_configs block)")
+    ap.add_argument("--no-all-configs", action="store_true", help="skip the per-workload block of the default run")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     import torch
     import paper_2511_12056_amd as pda
-    from synth import CONFIGS
-    from tests.util import gen_qkv_parallel, to_dev_bf16
+    from synth import CONFIGS, gen_qkv_parallel, to_dev_bf16
+
+    if args.config:
+        cs = torch.cuda.Stream()
+        r = measure_config(pda, torch, args.config, cs)
+        print(json.dumps({"metric": "attention TFLOP/s and % of bf16 MFMA peak (1 GPU), one workload", "value": r["tflops"],
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": r["iters"], "warmup": 3, "ms_per_step": r["median_ms"],
+                          "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                          "data": "synthetic", "config": {"workload": r["workload"]},
+                          "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": r["frac_of_bf16_peak"], "traffic": None}, "detail": r}))
+        return
 
     w, w5 = CONFIGS[4], CONFIGS[5]
     workers = min(16, os.cpu_count() or 8)
@@ -312,6 +394,11 @@ def main():
     if not args.no_next_rows:
         del qr, kc, kc_out, outq, lseq
         res["next_rows"] = next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, args.t_linear_ms)
+    if not args.no_all_configs:
+        # every workload of the benchmark spec through pda_attn_fwd, after the timed steps (not part of `value`)
+        # (C4 and C5 reuse the step's tensors: the first 3 and 6 heads of the C4 workload)
+        res["all_configs"] = {f"c{i}": measure_config(pda, torch, i, cs, tensors=((qb, kb, vb), (q, k, v)) if i >= 4 else None)
+                              for i in (1, 2, 3, 4, 5)}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, qb, kb, vb)
     print(json.dumps(res))

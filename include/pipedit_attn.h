@@ -2,11 +2,17 @@
  * libpipedit_attn: the attention hot path of PipeDiT video-DiT inference on MI355X (gfx950).
  *
  * C ABI.  Every pointer is a DEVICE pointer unless the comment says "host".
- * The caller owns every tensor.  The library itself keeps one small cached
- * device workspace per (device, stream) for partial results of pda_attn_fwd
- * (32 MB unless a launch needs more; allocated on first use, kept until the
- * process ends).  Work enqueued on one stream shares that stream's workspace,
- * which is safe because a stream runs its work in order.  All tensors are
+ * The caller owns every tensor.  The library itself keeps one device workspace
+ * per (device, stream) for the key-range partials of the d = 128 attention
+ * kernel (see pda_attn_tail_plan).  It is allocated once, the first time a
+ * launch on that stream needs one, with the largest size any launch can need
+ * on that device (768 slots of 132 096 bytes = 101 MB with 256 compute units);
+ * it never grows and is kept until the process ends, so after that first call
+ * per stream the attention entry points neither allocate nor free nor
+ * synchronise.  Work enqueued on one stream shares that stream's workspace,
+ * which is safe because a stream runs its work in order; calls on different
+ * streams use different workspaces.  If that one allocation fails the call
+ * returns PDA_ERR_NOMEM and launches nothing.  All tensors are
  * compact row-major for exactly the sizes passed:
  *
  *     q    [B, H, Sq,  d]  bf16        k, v [B, H, Skv, d]  bf16
@@ -39,7 +45,8 @@ typedef enum {
     PDA_OK = 0,
     PDA_ERR_INVALID_ARG = 1, /* null pointer, negative size, kv_valid_len > Skv, n < 1, ... */
     PDA_ERR_UNSUPPORTED = 2, /* d not in {64,128}, n > PDA_MAX_PARTIALS, misaligned pointer, size overflow */
-    PDA_ERR_HIP = 3          /* a HIP runtime call failed; see pda_last_error() */
+    PDA_ERR_HIP = 3,         /* a HIP runtime call failed; see pda_last_error() */
+    PDA_ERR_NOMEM = 4        /* the one-time device workspace of a stream could not be allocated */
 } pda_status;
 
 #define PDA_MAX_PARTIALS 16
@@ -65,7 +72,10 @@ typedef enum {
  *
  * Arithmetic: bf16 x bf16 products accumulated in fp32 on the matrix cores,
  * softmax statistics in fp32, probabilities rounded to bf16 before the PV
- * product.  Sq == 0 or B*H == 0 is a successful no-op.
+ * product.  Finite inputs give finite results as long as
+ * kv_valid_len * 2^8 * max|v| stays below the fp32 range (|v| up to 2^100 at
+ * any supported length); scores of any finite magnitude are handled.
+ * Sq == 0 or B*H == 0 is a successful no-op.
  */
 int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float* lse,
                  int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
@@ -89,6 +99,33 @@ int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out
                          int64_t out_batch_stride, int64_t out_head_stride,
                          int64_t lse_batch_stride, int64_t lse_head_stride,
                          float scale, int64_t kv_valid_len, int64_t q_offset, void* stream);
+
+/*
+ * How a d = 128 attention launch over B*H (batch, head) pairs is cut into work items (host only;
+ * every pointer below is a HOST pointer; no device work).  The kernel takes 256-row query tiles,
+ * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles
+ * (in (batch, head, query tile) order: the partly filled last round) are each computed as `split`
+ * partial attentions over key ranges of part_keys keys and merged with the formula of
+ * pda_attn_merge; all other tiles are swept in one pass.  Hence two launches agree bit for bit
+ * on every row that lies in an uncut tile of both, and to the rounding of the probabilities on
+ * the others.  n_cu: compute units of the device (0 = ask the current device).  Outputs (any may
+ * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_keys, and
+ * workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32 out).
+ * d = 64 launches and empty key sets are never cut.
+ */
+int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
+                       int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_keys, int64_t* workspace_slots);
+
+/*
+ * Testing aid: pda_attn_fwd (no q_offset) with an explicit choice of kernel for d = 128.
+ * variant 0 = what pda_attn_fwd runs; 1, 2 = two plain reference tilings of the same MFMA
+ * formulation (128 and 256 query rows per workgroup, register-staged double buffering, running
+ * max); 3 = variant 0 with its second, running-max sweep forced on every work item.  All compute
+ * the same function to rounding.  d = 64 ignores the variant.
+ */
+int pda_attn_fwd_variant(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, int variant, void* stream);
 
 /*
  * pda_attn_fwd with a bf16 output, for results that go straight on to the next projection and not
@@ -149,7 +186,7 @@ int pda_attn_merge(const float* const* partials, const float* const* lses, int n
  * over all heads agrees up to the rounding of probabilities: which query tiles
  * are computed as merged key-range partials depends on the launch size).
  *
- * sink: optional device [B,H,Sq,d] fp32 (NULL: the drain stream only waits).
+ * sink: optional device [B,H,Sq,d] fp32, not overlapping out (NULL: the drain stream only waits).
  * group_ms: optional HOST array of ceil(H/heads_per_group) floats receiving the
  * compute-stream time of each group; total_ms: optional HOST float receiving
  * the time from the first launch to the end of the last hand-off.  If either

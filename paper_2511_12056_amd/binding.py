@@ -12,7 +12,7 @@ from typing import Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpipedit_attn.so")
 
-PDA_OK, PDA_ERR_INVALID_ARG, PDA_ERR_UNSUPPORTED, PDA_ERR_HIP = 0, 1, 2, 3
+PDA_OK, PDA_ERR_INVALID_ARG, PDA_ERR_UNSUPPORTED, PDA_ERR_HIP, PDA_ERR_NOMEM = 0, 1, 2, 3, 4
 PDA_MAX_PARTIALS = 16
 PDA_MAX_LOCAL_HEADS = 64
 PDA_SINK_HEAD_MAJOR, PDA_SINK_TOKEN_ARRIVAL, PDA_SINK_TOKEN_FINAL = 0, 1, 2
@@ -39,6 +39,11 @@ def _load() -> C.CDLL:
     lib.pda_attn_fwd.restype = i32
     lib.pda_attn_fwd_strided.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32] + [i64] * 8 + [f32, i64, i64, vp]
     lib.pda_attn_fwd_strided.restype = i32
+    lib.pda_attn_fwd_variant.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i32, vp]
+    lib.pda_attn_fwd_variant.restype = i32
+    lib.pda_attn_tail_plan.argtypes = [i32, i32, i64, i64, i32, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32),
+                                       C.POINTER(i64), C.POINTER(i64)]
+    lib.pda_attn_tail_plan.restype = i32
     lib.pda_attn_merge.argtypes = [C.POINTER(vp), C.POINTER(vp), i32, fp, fp, i64, i32, vp]
     lib.pda_attn_merge.restype = i32
     lib.pda_headchunk_run.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i32, vp, vp, fp,
@@ -122,6 +127,30 @@ def attn_fwd(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None
     _check(lib.pda_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
                             n_v, int(q_offset), _stream_handle(stream)))
     return out, lse
+
+
+def attn_fwd_variant(q, k, v, out, lse, scale: float, variant: int, kv_valid_len: Optional[int] = None, stream=None):
+    """pda_attn_fwd_variant: attn_fwd with an explicit kernel choice (testing aid)."""
+    import torch
+    B, H, Sq, d = q.shape
+    Skv = k.shape[2]
+    _expect(q, torch.bfloat16, (B, H, Sq, d), "q")
+    _expect(k, torch.bfloat16, (B, H, Skv, d), "k")
+    _expect(v, torch.bfloat16, (B, H, Skv, d), "v")
+    _expect(out, torch.float32, (B, H, Sq, d), "out")
+    _expect(lse, torch.float32, (B, H, Sq), "lse")
+    n_v = Skv if kv_valid_len is None else int(kv_valid_len)
+    _check(lib.pda_attn_fwd_variant(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
+                                    n_v, int(variant), _stream_handle(stream)))
+    return out, lse
+
+
+def attn_tail_plan(B: int, H: int, Sq: int, kv_valid_len: int, d: int, n_cu: int = 0):
+    """pda_attn_tail_plan: dict(n_tiles, n_cut, split, part_keys, workspace_slots); n_cu = 0 asks the current device."""
+    a, b, c, e, f = C.c_int64(0), C.c_int64(0), C.c_int(0), C.c_int64(0), C.c_int64(0)
+    _check(lib.pda_attn_tail_plan(int(B), int(H), int(Sq), int(kv_valid_len), int(d), int(n_cu),
+                                  C.byref(a), C.byref(b), C.byref(c), C.byref(e), C.byref(f)))
+    return {"n_tiles": a.value, "n_cut": b.value, "split": c.value, "part_keys": e.value, "workspace_slots": f.value}
 
 
 def attn_fwd_bf16out(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None, stream=None):

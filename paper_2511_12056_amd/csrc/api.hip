@@ -2,8 +2,8 @@
 #include <hip/hip_runtime.h>
 #include <cmath>
 #include <cstdarg>
+#include <atomic>
 #include <cstdio>
-#include <cstdlib>
 #include <map>
 #include <mutex>
 #include <utility>
@@ -28,17 +28,6 @@ int hip_fail(hipError_t e, const char* what) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-// Tiling variant of the forward kernel; PDA_ATTN_VARIANT in the environment overrides the default
-// (a tuning and testing aid: every variant computes the same function; 1, 2 = reference tilings,
-// 3 = default kernel with its running-max sweep forced on every item).
-int attn_variant() {
-    static int v = [] {
-        const char* s = getenv("PDA_ATTN_VARIANT");
-        return s ? atoi(s) : 0;
-    }();
-    return v;
-}
 
 // Shared validation of the attention shape arguments.  Returns PDA_OK or an error code.
 int check_attn_args(const void* q, const void* k, const void* v, const float* out, const float* lse,
@@ -73,7 +62,7 @@ Strides compact_strides(int H, int64_t Sq, int64_t Skv, int d) {
 // base2: the scores q.k are already in log2 units (scale is then ln 2 and is not applied again).
 hipError_t launch_strided(const void* q, const void* k, const void* v, float* out, float* lse,
                           int B, int hg, int64_t Sq, int d, const Strides& s, float scale, int64_t n_v, hipStream_t st,
-                          bool base2 = false, bool out_bf16 = false) {
+                          int variant, bool base2, bool out_bf16, float* ws, int64_t ws_slots) {
     pda::AttnParams p{};
     p.q = static_cast<const __bf16*>(q);
     p.k = static_cast<const __bf16*>(k);
@@ -92,18 +81,106 @@ hipError_t launch_strided(const void* q, const void* k, const void* v, float* ou
     p.scale_log2e = base2 ? 1.0f : std::fmax(scale * 1.4426950408889634f, 1e-37f);
     p.base2 = base2 ? 1 : 0;
     p.out_bf16 = out_bf16 ? 1 : 0;
-    return pda::launch_attn_fwd(p, B * hg, d, attn_variant(), st);
+    return pda::launch_attn_fwd(p, B * hg, d, variant, ws, ws_slots, st);
 }
 
-// Launch attention for heads [h0, h0+hg) of compact [B,H,S,d] tensors.
-hipError_t launch_heads(const void* q, const void* k, const void* v, float* out, float* lse,
-                        int B, int H, int64_t Sq, int64_t Skv, int d, float scale, int64_t n_v,
-                        int h0, int hg, hipStream_t st) {
-    return launch_strided(static_cast<const __bf16*>(q) + (int64_t)h0 * Sq * d,
+}  // namespace
+
+namespace pda {
+
+hipError_t device_cu_count(int* n_cu) {
+    static std::atomic<int> cu[KernelSetup::MAX_DEV] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool cached = dev >= 0 && dev < KernelSetup::MAX_DEV;
+    int v = cached ? cu[dev].load(std::memory_order_acquire) : 0;
+    if (v == 0) {
+        if ((e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        if (cached) cu[dev].store(v, std::memory_order_release);
+    }
+    *n_cu = v;
+    return hipSuccess;
+}
+
+}  // namespace pda
+
+namespace {
+
+// ---- workspaces for the key-range partials of the software-pipelined kernel -------------------
+//
+// (1) Cached: one buffer per (device, stream), allocated the first time a launch on that stream
+// needs a workspace, with the largest size any launch can need on the device (a function of its CU
+// count alone: fewer than n_cu cut tiles, at most 4 ranges each), so it never grows, is never
+// freed and the launch path never synchronises.  Launches on one stream are ordered and share it.
+struct CachedWs { float* ptr; int64_t slots; };
+int cached_workspace(hipStream_t st, int64_t need_slots, CachedWs* out) {
+    static std::mutex mu;
+    static std::map<std::pair<int, hipStream_t>, CachedWs> pool;
+    int dev = 0, n_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = pda::device_cu_count(&n_cu);
+    if (e != hipSuccess) return hip_fail(e, "device query");
+    std::lock_guard<std::mutex> lock(mu);
+    CachedWs& w = pool[{dev, st}];
+    if (!w.ptr) {
+        const int64_t slots = pda::max_tail_slots(n_cu, true);
+        void* ptr = nullptr;
+        e = hipMalloc(&ptr, (size_t)slots * pda::kSlotFloats * sizeof(float));
+        if (e == hipErrorOutOfMemory) {
+            (void)hipGetLastError();
+            return fail(PDA_ERR_NOMEM, "no device memory for the %lld MB workspace of this stream",
+                        (long long)((size_t)slots * pda::kSlotFloats * sizeof(float) >> 20));
+        }
+        if (e != hipSuccess) return hip_fail(e, "workspace allocation");
+        w.ptr = static_cast<float*>(ptr);
+        w.slots = slots;
+    }
+    if (need_slots > w.slots) return fail(PDA_ERR_UNSUPPORTED, "launch needs %lld workspace slots, the stream's buffer has %lld", (long long)need_slots, (long long)w.slots);
+    *out = w;
+    return PDA_OK;
+}
+
+enum WsKind { WS_CACHED };
+
+// Validated attention launch for hg heads of B batches with the workspace the launch needs.
+int launch_checked(const void* q, const void* k, const void* v, float* out, float* lse,
+                   int B, int hg, int64_t Sq, int d, const Strides& s, float scale, int64_t n_v, hipStream_t st,
+                   int variant, bool base2, bool out_bf16, WsKind kind) {
+    float* ws = nullptr;
+    int64_t ws_slots = 0;
+    if (out_bf16 && variant != 3) variant = 0;           // only the software-pipelined kernel writes bf16
+    if (pda::uses_sp_kernel(d, variant, n_v)) {
+        int n_cu = 0;
+        hipError_t e = pda::device_cu_count(&n_cu);
+        if (e != hipSuccess) return hip_fail(e, "device query");
+        const int64_t need = pda::tail_slots(pda::plan_tail(Sq, B * hg, n_v, n_cu), out_bf16);
+        if (need > 0) {
+            CachedWs w{};
+            int rc = cached_workspace(st, need, &w);
+            if (rc != PDA_OK) return rc;
+            ws = w.ptr;
+            ws_slots = w.slots;
+        }
+    }
+    hipError_t e = launch_strided(q, k, v, out, lse, B, hg, Sq, d, s, scale, n_v, st, variant, base2, out_bf16, ws, ws_slots);
+    if (e != hipSuccess) return hip_fail(e, "attention launch");
+    return PDA_OK;
+}
+
+}  // namespace
+
+namespace {
+
+// Launch attention for heads [h0, h0+hg) of compact [B,H,S,d] tensors.  Returns a pda_status.
+int launch_heads(const void* q, const void* k, const void* v, float* out, float* lse,
+                 int B, int H, int64_t Sq, int64_t Skv, int d, float scale, int64_t n_v,
+                 int h0, int hg, hipStream_t st, int variant = 0, WsKind kind = WS_CACHED) {
+    return launch_checked(static_cast<const __bf16*>(q) + (int64_t)h0 * Sq * d,
                           static_cast<const __bf16*>(k) + (int64_t)h0 * Skv * d,
                           static_cast<const __bf16*>(v) + (int64_t)h0 * Skv * d,
                           out + (int64_t)h0 * Sq * d, lse + (int64_t)h0 * Sq,
-                          B, hg, Sq, d, compact_strides(H, Sq, Skv, d), scale, n_v, st);
+                          B, hg, Sq, d, compact_strides(H, Sq, Skv, d), scale, n_v, st, variant, false, false, kind);
 }
 
 // The head-chunk pipeline (Algorithm 1, steps 2-9) over the given groups; arguments already validated.
@@ -113,7 +190,12 @@ int run_pipeline(const void* q, const void* k, const void* v, float* out, float*
                  void* compute_stream, void* drain_stream, float* sink, float* group_ms, float* total_ms) {
     if (compute_stream == drain_stream) return fail(PDA_ERR_INVALID_ARG, "compute and drain streams must differ");
     if (sink && !aligned16(sink)) return fail(PDA_ERR_UNSUPPORTED, "sink must be 16-byte aligned");
-    if (sink && sink == out) return fail(PDA_ERR_INVALID_ARG, "sink must not alias out");
+    if (sink) {
+        const char* o0 = reinterpret_cast<const char*>(out);
+        const char* s0 = reinterpret_cast<const char*>(sink);
+        const size_t bytes = (size_t)B * H * Sq * d * sizeof(float);
+        if (o0 < s0 + bytes && s0 < o0 + bytes) return fail(PDA_ERR_INVALID_ARG, "sink must not overlap out");
+    }
     const int n_groups = (int)sizes.size();
     if (B == 0 || H == 0 || Sq == 0) {
         if (total_ms) *total_ms = 0.f;
@@ -142,10 +224,11 @@ int run_pipeline(const void* q, const void* k, const void* v, float* out, float*
     if (e != hipSuccess) { cleanup(); return hip_fail(e, "event creation"); }
 
     const int h_local = H / sp_ranks;
+    int rc = PDA_OK;
     for (int g = 0, h0 = 0; g < n_groups; h0 += sizes[g], ++g) {
         const int hg = sizes[g];
         if (timed && (e = hipEventRecord(beg[g], cs)) != hipSuccess) break;
-        if ((e = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, h0, hg, cs)) != hipSuccess) break;
+        if ((rc = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, h0, hg, cs)) != PDA_OK) break;
         if ((e = hipEventRecord(done[g], cs)) != hipSuccess) break;
         if ((e = hipStreamWaitEvent(ds, done[g], 0)) != hipSuccess) break;
         if (sink) {
@@ -162,12 +245,12 @@ int run_pipeline(const void* q, const void* k, const void* v, float* out, float*
             if (e != hipSuccess) break;
         }
     }
-    if (e == hipSuccess && timed) e = hipEventRecord(drain_end, ds);
-    if (e != hipSuccess) {
+    if (rc == PDA_OK && e == hipSuccess && timed) e = hipEventRecord(drain_end, ds);
+    if (rc != PDA_OK || e != hipSuccess) {
         (void)hipStreamSynchronize(cs);
         (void)hipStreamSynchronize(ds);
         cleanup();
-        return hip_fail(e, "head-chunk pipeline");
+        return rc != PDA_OK ? rc : hip_fail(e, "head-chunk pipeline");   // rc: the message is already set
     }
     if (timed) {
         if ((e = hipStreamSynchronize(cs)) == hipSuccess) e = hipStreamSynchronize(ds);
@@ -191,40 +274,11 @@ int run_pipeline(const void* q, const void* k, const void* v, float* out, float*
 
 }  // namespace
 
-namespace pda {
-
-hipError_t attn_workspace(hipStream_t st, size_t bytes, float** out) {
-    struct Buf { void* ptr; size_t size; };
-    static std::mutex mu;
-    static std::map<std::pair<int, hipStream_t>, Buf> pool;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    std::lock_guard<std::mutex> lock(mu);
-    Buf& b = pool[{dev, st}];
-    if (b.size < bytes) {
-        if (b.ptr) {
-            // the old buffer may still be read by work queued on this stream
-            if ((e = hipStreamSynchronize(st)) != hipSuccess) return e;
-            (void)hipFree(b.ptr);
-            b.ptr = nullptr;
-            b.size = 0;
-        }
-        size_t want = bytes < (size_t)(32u << 20) ? (size_t)(32u << 20) : bytes;
-        if ((e = hipMalloc(&b.ptr, want)) != hipSuccess) return e;
-        b.size = want;
-    }
-    *out = static_cast<float*>(b.ptr);
-    return hipSuccess;
-}
-
-}  // namespace pda
-
 extern "C" {
 
 const char* pda_last_error(void) { return g_err; }
 
-int pda_version(void) { return 200; }
+int pda_version(void) { return 300; }
 
 int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float* lse,
                  int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
@@ -233,9 +287,37 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
     if (rc != PDA_OK) return rc;
     if (q_offset < 0) return fail(PDA_ERR_INVALID_ARG, "q_offset=%lld is negative", (long long)q_offset);
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
-    hipError_t e = launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H,
-                                static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return hip_fail(e, "attention launch");
+    return launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H, static_cast<hipStream_t>(stream));
+}
+
+int pda_attn_fwd_variant(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, int variant, void* stream) {
+    int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len);
+    if (rc != PDA_OK) return rc;
+    if (variant < 0 || variant > 3) return fail(PDA_ERR_INVALID_ARG, "variant=%d (0..3)", variant);
+    if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
+    return launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H, static_cast<hipStream_t>(stream), variant);
+}
+
+int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
+                       int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_keys, int64_t* workspace_slots) {
+    if (B < 0 || H < 0 || Sq < 0 || kv_valid_len < 0) return fail(PDA_ERR_INVALID_ARG, "negative size");
+    if (d != 64 && d != 128) return fail(PDA_ERR_UNSUPPORTED, "head dim d=%d not supported (64 or 128)", d);
+    if ((int64_t)B * H > 65535) return fail(PDA_ERR_UNSUPPORTED, "B*H > 65535");
+    if (n_cu < 0) return fail(PDA_ERR_INVALID_ARG, "n_cu=%d is negative", n_cu);
+    if (n_cu == 0) {
+        hipError_t e = pda::device_cu_count(&n_cu);
+        if (e != hipSuccess) return hip_fail(e, "device query");
+    }
+    pda::TailPlan t{};
+    t.split = 1;
+    if (pda::uses_sp_kernel(d, 0, kv_valid_len) && (int64_t)B * H * Sq > 0) t = pda::plan_tail(Sq, B * H, kv_valid_len, n_cu);
+    if (n_tiles) *n_tiles = t.n_tiles;
+    if (n_cut) *n_cut = t.n_cut;
+    if (split) *split = t.split;
+    if (part_keys) *part_keys = t.part_keys;
+    if (workspace_slots) *workspace_slots = pda::tail_slots(t, false);
     return PDA_OK;
 }
 
@@ -246,10 +328,8 @@ int pda_attn_fwd_bf16out(const void* q, const void* k, const void* v, void* out,
     if (rc != PDA_OK) return rc;
     if (d != 128) return fail(PDA_ERR_UNSUPPORTED, "a bf16 output needs d = 128 (got %d)", d);
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
-    hipError_t e = launch_strided(q, k, v, static_cast<float*>(out), lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d),
-                                  scale, kv_valid_len, static_cast<hipStream_t>(stream), false, true);
-    if (e != hipSuccess) return hip_fail(e, "attention launch");
-    return PDA_OK;
+    return launch_checked(q, k, v, static_cast<float*>(out), lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d),
+                          scale, kv_valid_len, static_cast<hipStream_t>(stream), 0, false, true, WS_CACHED);
 }
 
 int pda_attn_fwd_base2(const void* q, const void* k, const void* v, float* out, float* lse,
@@ -258,10 +338,8 @@ int pda_attn_fwd_base2(const void* q, const void* k, const void* v, float* out, 
     int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, ln2, kv_valid_len);
     if (rc != PDA_OK) return rc;
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
-    hipError_t e = launch_strided(q, k, v, out, lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d), ln2, kv_valid_len,
-                                  static_cast<hipStream_t>(stream), true);
-    if (e != hipSuccess) return hip_fail(e, "attention launch");
-    return PDA_OK;
+    return launch_checked(q, k, v, out, lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d), ln2, kv_valid_len,
+                          static_cast<hipStream_t>(stream), 0, true, false, WS_CACHED);
 }
 
 int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out, float* lse,
@@ -285,9 +363,8 @@ int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out
     if (B > 1 && (s.o_bs < (int64_t)(H - 1) * s.o_hs + Sq * d || s.l_bs < (int64_t)(H - 1) * s.l_hs + Sq))
         return fail(PDA_ERR_INVALID_ARG, "batches of out/lse overlap (batch stride too small)");
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
-    hipError_t e = launch_strided(q, k, v, out, lse, B, H, Sq, d, s, scale, kv_valid_len, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return hip_fail(e, "attention launch");
-    return PDA_OK;
+    return launch_checked(q, k, v, out, lse, B, H, Sq, d, s, scale, kv_valid_len, static_cast<hipStream_t>(stream),
+                          0, false, false, WS_CACHED);
 }
 
 int pda_attn_merge(const float* const* partials, const float* const* lses, int n,
@@ -419,8 +496,11 @@ int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_
     int dev = 0, n_cu = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-    float* sink = nullptr;
-    if (e == hipSuccess) e = pda::attn_workspace(st, 512 * sizeof(float), &sink);
+    if (e != hipSuccess) return hip_fail(e, "device query");
+    CachedWs w{};
+    int rc = cached_workspace(st, 1, &w);            // one slot is far more than the 512 floats needed
+    if (rc != PDA_OK) return rc;
+    float* sink = w.ptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (e == hipSuccess) e = hipEventCreate(&e0);
     if (e == hipSuccess) e = hipEventCreate(&e1);

@@ -308,7 +308,7 @@ static hipError_t launch_variant(const AttnParams& p, int BH, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipStream_t st) {
+hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, float* ws, int64_t ws_slots, hipStream_t st) {
     if (p.n_v == 0) {
         dim3 grid((unsigned)((p.Sq * D + 255) / 256 < 4096 ? (p.Sq * D + 255) / 256 : 4096), (unsigned)BH);
         hipLaunchKernelGGL(attn_empty_kernel, grid, dim3(256), 0, st, p, D);
@@ -322,9 +322,9 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipS
         case 3: {                                                      // software-pipelined kernel, second sweep forced
             AttnParams r = p;
             r.redo_always = 1;
-            return launch_attn_fwd_sp(r, BH, st);
+            return launch_attn_fwd_sp(r, BH, ws, ws_slots, st);
         }
-        default: return launch_attn_fwd_sp(p, BH, st);                 // software-pipelined kernel
+        default: return launch_attn_fwd_sp(p, BH, ws, ws_slots, st);                 // software-pipelined kernel
     }
 }
 

@@ -24,7 +24,8 @@
 // exponent range) leaves a wide margin.  The item is therefore first swept with a FIXED reference per
 // row, the max of the row's scores in the first key tile: no max pass, no rescaling of O, weights
 // may exceed 1.  If a row's sum ends up beyond 2^64 (some later score lay that far above the
-// first tile, or the input held non-finite values) the workgroup sweeps the item again with the
+// first tile, or the input held non-finite values), or an output accumulator is not finite (large
+// weights times large V entries), the workgroup sweeps the item again with the
 // usual running max, where the reference moves only when the max grew by more than 2^8 and O is
 // rescaled after the stream in a rare wave-uniform branch.  The row sum is taken with plain fp32
 // adds on the unrounded probabilities; the dot-product instructions (v_dot2c_f32_bf16), which
@@ -32,9 +33,10 @@
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), four buffers per
 // tensor; the loop is unrolled four times so that every buffer offset is an immediate.  At the
-// end of iteration t a wavefront issues its share of K tile t+4 (over K tile t) and V tile t+2
-// (over V tile t-2); before the barrier that closes the iteration it waits for all but its two
-// newest batches, i.e. for K tile t+2 and V tile t, which iteration t+1 reads.
+// top of iteration t a wavefront issues its share of K tile t+4 (over K tile t) and V tile t+2
+// (over V tile t-2), both last read in iteration t-1; before the barrier that closes the
+// iteration it waits for all but its two newest batches, i.e. for K tile t+2 and V tile t, which
+// iteration t+1 reads.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "attn_internal.h"
@@ -47,13 +49,12 @@ namespace pda {
 // on purpose: the compiler's wait-count insertion then does not see an LDS write that it cannot
 // tell apart from the operand reads that follow (it would drain the whole prefetch before every
 // LDS read); completion is tracked by hand with s_waitcnt vmcnt before the barrier.
-// M0 is not restored: nothing else in this kernel uses it (LDS instructions on gfx9+ do not), and
-// the compiler is told nothing about it, so keep any M0-dependent builtin out of this file.
+// M0 is not restored; it is declared clobbered.
 __device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // Same with the LDS address given as wave-uniform base + compile-time offset.
@@ -62,7 +63,7 @@ __device__ __forceinline__ void lds_dma16_at(const void* sbase, unsigned voff, u
     asm volatile("s_add_u32 m0, %0, %1\n\tglobal_load_lds_dwordx4 %2, %3"
                  :
                  : "s"(lds_base), "n"(LDS_OFF), "v"(voff), "s"(sbase)
-                 : "memory", "scc");
+                 : "memory", "scc", "m0");
 }
 
 template <int N>
@@ -502,10 +503,9 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                     for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+a"(qf[nq][kk]));
                 }
             }
-            // This iteration's DMA batch: K tile t+4 over K tile t, V tile t+2 over V tile t-2 (both last
-            // read in iteration t-1).  Issued here, where the wavefronts of a workgroup arrive spread
-            // out in time, rather than right after the barrier where all of them would queue up at once.
-            wait_vmcnt<4 * CPW>();      // all but the two newest batches (this and the previous iteration's)
+            // Of the DMA batches in flight, all but the two newest (this iteration's, issued at its top,
+            // and the previous one's) must have landed: K tile t+2 and V tile t, which iteration t+1 reads.
+            wait_vmcnt<4 * CPW>();
             barrier();
         };
 
@@ -524,10 +524,21 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     sweep(std::false_type{});
     {
         // A row whose sum left the safe range (a later score exceeded the first tile's max by more
-        // than ~2^64, or non-finite input) makes the whole workgroup redo the item with the running max.
+        // than ~2^64, or non-finite input) or whose accumulators are not finite makes the whole
+        // workgroup redo the item with the running max (weights <= 2^8 there).
         bool bad = p.redo_always != 0;               // test switch: every item takes the second sweep
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) bad |= !(pair_sum(l_run[nq]) < 1.8446744e19f);
+        for (int nq = 0; nq < NQ; ++nq) {
+            bad |= !(pair_sum(l_run[nq]) < 1.8446744e19f);
+            // Weights of up to 2^64 times large finite V entries can overflow the accumulators while the
+            // row sum stays in range: inf * 0 and NaN * 0 are NaN, any finite value * 0 is 0.
+            float t = 0.f;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) t = __builtin_fmaf(o_acc[nq][db][r], 0.0f, t);
+            bad |= !(t == 0.f);
+        }
         const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
         barrier();                                   // every wavefront is done with the LDS tiles and its DMA
         LDS_PTR(volatile int) flags = (LDS_PTR(volatile int))smem;
@@ -615,7 +626,7 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
 }
 
 template <int NQ, bool BASE2>
-static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
+static hipError_t launch_sp(AttnParams p, int BH, float* ws, int64_t ws_slots, hipStream_t st) {
     constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
     constexpr int M = 256, D = 128;
     auto kern = attn_fwd_sp_kernel<NQ, BASE2>;
@@ -625,50 +636,25 @@ static hipError_t launch_sp(AttnParams p, int BH, hipStream_t st) {
         hipError_t e = setup.ensure(reinterpret_cast<const void*>(kern), smem, &n_cu);
         if (e != hipSuccess) return e;
     }
-    // Work plan: one workgroup per CU at a time, so tiles run in rounds of n_cu and a partly
-    // filled last round wastes the rest of the machine.  The tiles of the last round are cut into
-    // `split` key ranges (at most 4, each at least 8 key tiles long), so that the tail is made of
-    // shorter items; they may spill over one round of such items.  Cost of the tail in tile-times:
-    // ceil(rem * split / n_cu) / split, plus a small charge per cut tile for the partial stores
-    // and the merge pass.  (Cutting tiles of earlier, full rounds as well never lowers that cost.)
-    p.tiles_per_head = (int)((p.Sq + M - 1) / M);
-    const int64_t n_tiles = (int64_t)p.tiles_per_head * BH;
-    const int rem = (int)(n_tiles % n_cu);
-    int split = 1;
-    if (rem) {
-        double best = 1.0;
-        for (int s = 2; s <= 4 && p.n_v >= (int64_t)s * 8 * 64; ++s) {
-            const double cost = (double)(((int64_t)rem * s + n_cu - 1) / n_cu) / s + 0.02 * rem / n_cu;
-            if (cost < best - 1e-9) { best = cost; split = s; }
-        }
-    }
-    const int64_t n_cut = split > 1 ? rem : 0;
-    p.split = split;
-    p.n_full = (int)n_tiles;
-    p.part_keys = 0;
-    p.part_out = nullptr;
-    p.part_lse = nullptr;
-    int64_t items = n_tiles;
-    if (split > 1) {
-        p.n_full = (int)(n_tiles - n_cut);
-        p.part_keys = ((p.n_v + split - 1) / split + 63) / 64 * 64;
-        const size_t slots = (size_t)n_cut * (p.out_bf16 ? split : split - 1);
-        float* ws = nullptr;
-        hipError_t e = attn_workspace(st, slots * (M * D + M) * sizeof(float), &ws);
-        if (e != hipSuccess) return e;
-        p.part_out = ws;
-        p.part_lse = ws + slots * (M * D);
-        items = p.n_full + n_cut * split;
-    }
+    const TailPlan t = plan_tail(p.Sq, BH, p.n_v, n_cu);
+    const int64_t slots = tail_slots(t, p.out_bf16 != 0);
+    if (slots > 0 && (ws == nullptr || slots > ws_slots)) return hipErrorInvalidValue;
+    p.tiles_per_head = t.tiles_per_head;
+    p.split = t.split;
+    p.n_full = (int)(t.n_tiles - t.n_cut);
+    p.part_keys = t.part_keys;
+    p.part_out = slots ? ws : nullptr;
+    p.part_lse = slots ? ws + slots * (M * D) : nullptr;
+    const int64_t items = p.n_full + t.n_cut * t.split;
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(512 / NQ), smem, st, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || split <= 1) return e;
-    hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(n_cut * (M / 8))), dim3(256), 0, st, p, (int)n_cut);
+    if (e != hipSuccess || t.split <= 1) return e;
+    hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(t.n_cut * (M / 8))), dim3(256), 0, st, p, (int)t.n_cut);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, hipStream_t st) {
-    return p.base2 ? launch_sp<1, true>(p, BH, st) : launch_sp<1, false>(p, BH, st);
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, float* ws, int64_t ws_slots, hipStream_t st) {
+    return p.base2 ? launch_sp<1, true>(p, BH, ws, ws_slots, st) : launch_sp<1, false>(p, BH, ws, ws_slots, st);
 }
 
 }  // namespace pda

@@ -63,15 +63,73 @@ struct AttnParams {
     int redo_always;        // software-pipelined kernel: sweep every item a second time with the running max (testing aid)
 };
 
-// Enqueue the forward kernel for B*Hg = BH (batch, head) pairs.  variant selects a tiling (0 = default).
-hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, hipStream_t st);
+// Tail plan of the software-pipelined kernel (d = 128, 256-row query tiles, one workgroup per CU
+// at a time, so tiles run in rounds of n_cu).  The tiles of the last, partly filled round are cut
+// into `split` key ranges (2..4, each at least 8 key tiles long) so that the tail is made of
+// shorter items; they may spill over one round of such items.  Cost of the tail in tile-times:
+// ceil(rem * split / n_cu) / split, plus a small charge per cut tile for the partial stores and
+// the merge pass (cutting tiles of earlier, full rounds as well never lowers that cost).
+// A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
+// the last n_cut of the launch's n_tiles tiles in (batch, head, query tile) order.
+struct TailPlan {
+    int tiles_per_head;
+    int64_t n_tiles;
+    int64_t n_cut;          // 0 if no tile is cut
+    int split;              // 1 if no tile is cut
+    int64_t part_keys;      // keys per range (multiple of 64); 0 if no tile is cut
+};
+inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
+    TailPlan t{};
+    t.tiles_per_head = (int)((Sq + 255) / 256);
+    t.n_tiles = (int64_t)t.tiles_per_head * BH;
+    t.split = 1;
+    const int rem = (int)(t.n_tiles % n_cu);
+    if (rem) {
+        double best = 1.0;
+        for (int s = 2; s <= 4 && n_v >= (int64_t)s * 8 * 64; ++s) {
+            const double cost = (double)(((int64_t)rem * s + n_cu - 1) / n_cu) / s + 0.02 * rem / n_cu;
+            if (cost < best - 1e-9) { best = cost; t.split = s; }
+        }
+    }
+    if (t.split > 1) {
+        t.n_cut = rem;
+        t.part_keys = ((n_v + t.split - 1) / t.split + 63) / 64 * 64;
+    }
+    return t;
+}
+// One workspace slot holds one key-range partial of a cut tile: 256 x 128 values + 256 lse.
+constexpr size_t kSlotFloats = 256 * 128 + 256;
+// Slots a launch needs: parts 1.. of every cut tile (part 0 goes to out/lse), or all parts when
+// out is bf16 (the merge pass then needs part 0 in fp32 as well).
+inline int64_t tail_slots(const TailPlan& t, bool out_bf16) {
+    return t.split > 1 ? t.n_cut * (out_bf16 ? t.split : t.split - 1) : 0;
+}
+// Largest slot count any launch can need on a device with n_cu compute units.
+inline int64_t max_tail_slots(int n_cu, bool out_bf16) {
+    int64_t m = 0;
+    for (int rem = 1; rem < n_cu; ++rem) {
+        TailPlan t = plan_tail(256, rem, (int64_t)1 << 20, n_cu);
+        const int64_t s = tail_slots(t, out_bf16);
+        if (s > m) m = s;
+    }
+    return m;
+}
+
+// Enqueue the forward kernel for B*Hg = BH (batch, head) pairs.  variant selects a tiling (0 = the
+// software-pipelined kernel for d = 128; 1, 2 = reference tilings; 3 = 0 with its running-max sweep
+// forced on every item).  ws / ws_slots: device workspace for the key-range partials of the
+// software-pipelined kernel and its capacity in slots of kSlotFloats floats; a launch that needs
+// more returns hipErrorInvalidValue (the caller sizes it with plan_tail / tail_slots).
+hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, float* ws, int64_t ws_slots, hipStream_t st);
 
 // Software-pipelined kernel for d = 128 (attn_fwd_sp.hip); p.n_v >= 1, p.scale_log2e > 0.
-hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, hipStream_t st);
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, float* ws, int64_t ws_slots, hipStream_t st);
 
-// Device workspace of at least `bytes` bytes for work enqueued on stream st (one cached buffer per
-// stream, grown on demand; work on one stream is ordered, so consecutive launches may share it).
-hipError_t attn_workspace(hipStream_t st, size_t bytes, float** out);
+// Does this (d, variant, valid key count) take the software-pipelined kernel (and so possibly a workspace)?
+inline bool uses_sp_kernel(int D, int variant, int64_t n_v) { return D == 128 && n_v > 0 && (variant == 0 || variant == 3); }
+
+// CU count of the current device (cached per device).
+hipError_t device_cu_count(int* n_cu);
 
 struct MergeParams {
     const float* part[16];

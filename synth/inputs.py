@@ -96,3 +96,26 @@ def gen_qkv(seed: int, B: int, H: int, Sq: int, Skv: int, d: int, *, unit_rms: b
     k = gen_tensor(seed, K_ID, (B, H, Skv, d), unit_rms=unit_rms, heads=heads)
     v = gen_tensor(seed, V_ID, (B, H, Skv, d), unit_rms=unit_rms, heads=heads)
     return q, k, v
+
+
+def gen_qkv_parallel(w, heads=None, workers: int = 8):
+    """q, k, v payloads of workload w (optionally a head range), generated head by head in threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    h0, h1 = heads if heads is not None else (0, w.H)
+    jobs = [(tid, S, h) for tid, S in ((Q_ID, w.Sq), (K_ID, w.Skv), (V_ID, w.Skv)) for h in range(h0, h1)]
+
+    def run(job):
+        tid, S, h = job
+        return gen_tensor(w.seed, tid, (w.B, w.H, S, w.d), unit_rms=w.unit_rms, heads=(h, h + 1))
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        parts = list(ex.map(run, jobs))
+    n = h1 - h0
+    return (np.concatenate(parts[0:n], axis=1), np.concatenate(parts[n:2 * n], axis=1),
+            np.concatenate(parts[2 * n:3 * n], axis=1))
+
+
+def to_dev_bf16(bits: np.ndarray):
+    """Upload uint16 bf16 payloads as a torch.bfloat16 tensor on the current GPU (same bits)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()

@@ -23,7 +23,9 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
-    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_bf16out", "pda_attn_fwd_strided", "pda_attn_merge", "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
+    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_bf16out", "pda_attn_fwd_strided",
+                     "pda_attn_fwd_variant", "pda_attn_merge", "pda_attn_tail_plan",
+                     "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
                      "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_mfma_rate", "pda_version"]
     lib = C.CDLL(pda.lib_path())
@@ -79,7 +81,9 @@ def test_headchunk_rejects_bad_arguments(pda):
     args = [16, 16, 16, 16, 16, 1, 4, 8, 8, 64, 1.0, 8]
     assert f(*args, 0, 16, 32, None, None, None) == 1 and "heads_per_group" in pda.last_error()
     assert f(*args, 2, 16, 16, None, None, None) == 1 and "streams" in pda.last_error()
-    assert f(*args, 2, 16, 32, 16, None, None) == 1 and "alias" in pda.last_error()      # sink == out
+    assert f(*args, 2, 16, 32, 16, None, None) == 1 and "overlap" in pda.last_error()    # sink == out
+    assert f(*args, 2, 16, 32, 16 + 1024, None, None) == 1 and "overlap" in pda.last_error()   # sink inside out (8 KB)
+    assert f(*(args[:7] + [0] + args[8:]), 2, 16, 32, 16 + 8192, None, None) == 0              # Sq = 0: nothing to overlap
     assert f(*args[:9], 48, 1.0, 8, 2, 16, 32, None, None, None) == 2
     # an empty problem reports zero times
     gms = (C.c_float * 2)(1.0, 1.0)
@@ -201,3 +205,40 @@ def test_bf16out_rejects_bad_arguments(pda):
     assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 9, None) == 1
     assert f(128, 128, 128, None, 128, 1, 1, 8, 8, 128, 1.0, 8, None) == 1
     assert f(None, None, None, None, None, 0, 1, 8, 8, 128, 1.0, 8, None) == 0
+
+
+def test_variant_entry_rejects_bad_arguments(pda):
+    f = pda.lib.pda_attn_fwd_variant
+    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 8, 4, None) == 1 and "variant" in pda.last_error()
+    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 8, -1, None) == 1
+    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 32, 1.0, 8, 1, None) == 2
+    assert f(None, None, None, None, None, 1, 1, 0, 8, 128, 1.0, 8, 2, None) == 0
+
+
+def test_tail_plan_matches_the_rule_restated_in_python(pda):
+    """pda_attn_tail_plan is host arithmetic: compare it with the rule written out independently
+    (tests/util.py: tail_plan) over a sweep of launch sizes and CU counts, and pin the plans of the
+    workloads (256 compute units)."""
+    from tests.util import tail_plan
+    import numpy as np
+    rng = np.random.default_rng(5)
+    for _ in range(3000):
+        n_cu = int(rng.choice([256, 304, 64, 1, 7]))
+        BH = int(rng.integers(1, 40))
+        Sq = int(rng.integers(1, 200000)) if rng.random() < 0.3 else int(rng.integers(1, 5000))
+        n_v = int(rng.choice([0, 1, 511, 512, 1023, 1024, 1535, 1536, 2047, 2048, int(rng.integers(1, 200000))]))
+        d = int(rng.choice([64, 128]))
+        got = pda.attn_tail_plan(1, BH, Sq, n_v, d, n_cu)
+        want = tail_plan(BH, Sq, n_v, d, n_cu)
+        assert got == want, (n_cu, BH, Sq, n_v, d, got, want)
+    # the workloads: one 3-head group at 720p is 1 398 tiles = 5 rounds + 118 tiles, cut in 2
+    assert pda.attn_tail_plan(1, 3, 119056, 119056, 128, 256) == {
+        "n_tiles": 1398, "n_cut": 118, "split": 2, "part_keys": 59584, "workspace_slots": 118}
+    # 24 heads x 9 600: 912 tiles = 3 rounds + 144, cut in 3 (two rounds of thirds)
+    assert pda.attn_tail_plan(1, 24, 9600, 9600, 128, 256) == {
+        "n_tiles": 912, "n_cut": 144, "split": 3, "part_keys": 3200, "workspace_slots": 288}
+    # d = 64 and an empty key set are never cut
+    assert pda.attn_tail_plan(1, 2, 1024, 1024, 64, 256)["split"] == 1
+    assert pda.attn_tail_plan(1, 3, 5000, 0, 128, 256)["n_cut"] == 0
+    assert pda.lib.pda_attn_tail_plan(1, 1, 8, 8, 32, 256, None, None, None, None, None) == 2
+    assert pda.lib.pda_attn_tail_plan(1, 1, -1, 8, 128, 256, None, None, None, None, None) == 1

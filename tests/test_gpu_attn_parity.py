@@ -200,44 +200,97 @@ def test_scores_far_above_the_first_tile_take_the_running_max_path():
         assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, f"overflow redo n_v={n_v}")
 
 
-def test_reference_tilings_and_forced_second_sweep_agree_with_the_oracle(tmp_path):
-    """PDA_ATTN_VARIANT selects the reference tilings (1, 2) or forces the default kernel's
-    running-max sweep on every item (3).  The switch is read once per process, so each variant runs
-    in a small child process; its results are checked here against the oracle."""
-    import subprocess
-    import sys
+def test_reference_tilings_and_forced_second_sweep_agree_with_the_oracle():
+    """pda_attn_fwd_variant selects the reference tilings (1, 2) or forces the default kernel's
+    running-max sweep on every item (3); all of them against the oracle."""
+    import torch
+    import paper_2511_12056_amd as pda
     from oracle import attention
-    shapes = [(1, 2, 515, 1100, 1050, 0.09), (2, 1, 300, 4200, 4200, 0.3), (1, 3, 777, 64, 40, 0.0883883)]
-    child = r'''
-import sys, numpy as np, torch
-sys.path.insert(0, sys.argv[1])
-import paper_2511_12056_amd as pda
-from synth import gen_qkv
-from tests.util import to_dev_bf16
-shapes = eval(sys.argv[3])
-res = {}
-for i, (B, H, Sq, Skv, n_v, scale) in enumerate(shapes):
-    qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, 128, unit_rms=bool(i % 2))
-    out = torch.full((B, H, Sq, 128), float("nan"), device="cuda"); lse = torch.full((B, H, Sq), float("nan"), device="cuda")
-    pda.attn_fwd(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out, lse, scale, n_v)
-    torch.cuda.synchronize()
-    res[f"o{i}"] = out.cpu().numpy(); res[f"l{i}"] = lse.cpu().numpy()
-np.savez(sys.argv[2], **res)
-'''
-    import os
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    refs = []
+    shapes = [(1, 2, 515, 1100, 1050, 0.09), (2, 1, 300, 4200, 4200, 0.3), (1, 3, 777, 64, 40, 0.0883883),
+              (1, 24, 700, 3000, 2990, 0.0883883)]                  # the last one: every tile cut in three
     for i, (B, H, Sq, Skv, n_v, scale) in enumerate(shapes):
         qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, 128, unit_rms=bool(i % 2))
-        refs.append(attention(qb, kb, vb, scale, n_v))
-    for variant in ("1", "2", "3"):
-        f = str(tmp_path / f"v{variant}.npz")
-        env = dict(os.environ, PDA_ATTN_VARIANT=variant)
-        print("variant", variant, flush=True)
-        subprocess.run([sys.executable, "-c", child, root, f, repr(shapes)], check=True, env=env, timeout=200)
-        got = np.load(f)
-        for i, (ro, rl) in enumerate(refs):
-            assert_close(got[f"o{i}"], got[f"l{i}"], ro, rl, f"variant {variant} shape {i}")
+        ro, rl = attention(qb, kb, vb, scale, n_v)
+        q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+        for variant in (0, 1, 2, 3):
+            out = torch.full((B, H, Sq, 128), float("nan"), device="cuda"); lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+            print("variant", variant, "shape", i, flush=True)
+            pda.attn_fwd_variant(q, k, v, out, lse, scale, variant, n_v)
+            torch.cuda.synchronize()
+            assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, f"variant {variant} shape {i}")
+
+
+def test_large_finite_values_take_the_running_max_path():
+    """With the fixed reference of the first sweep the weights may reach 2^64; times finite V entries
+    of magnitude up to 2^100 that overflows the output accumulators although every row sum stays in
+    range.  Such items must be redone with the running max (weights <= 2^8), where the result is
+    finite like the oracle's.  Scores rise by tens of log2 units after the first key tile."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    rng = np.random.default_rng(99)
+    B, H, Sq, Skv, d = 1, 3, 520, 1300, 128
+    q = rng.standard_normal((B, H, Sq, d)).astype(np.float32)
+    k = (rng.standard_normal((B, H, Skv, d)) * 0.05).astype(np.float32)
+    v = rng.standard_normal((B, H, Skv, d)).astype(np.float32)
+    k[:, 0, 64:] *= 12.0                                   # head 0: scores grow ~40 log2 units after the first tile
+    k[0, 1, 700] = q[0, 1, 9] * 0.45                       # head 1: one key ~50 above everything for query row 9
+    v[:, 0] *= np.float32(2.0 ** 100)                      # head 0: huge values everywhere
+    v[:, 1] *= np.float32(2.0 ** 90)
+    v[0, 2, 5::7] *= np.float32(2.0 ** 100)                # head 2: ordinary scores, some huge values (no overflow: weights <= ~2^10)
+    qb, kb, vb = f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v)
+    out = torch.full((B, H, Sq, d), float("nan"), device="cuda")
+    lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+    pda.attn_fwd(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), out, lse, 1.0)
+    torch.cuda.synchronize()
+    ro, rl = attention(qb, kb, vb, 1.0)
+    o, l = out.cpu().numpy().astype(np.float64), lse.cpu().numpy()
+    assert np.isfinite(ro).all() and np.isfinite(o).all() and np.isfinite(l).all()
+    s = bf16_bits_to_f32(kb[0, 0]).astype(np.float64) @ bf16_bits_to_f32(qb[0, 0]).astype(np.float64).T
+    assert (s[64:].max(axis=0) - s[:64].max(axis=0)).max() > 30    # the inputs do what they are meant to (natural-log units)
+    for h in range(H):                                      # relative gates: the values span 2^100
+        ref = ro[0, h]
+        assert np.sqrt(((o[0, h] - ref) ** 2).sum() / (ref ** 2).sum()) <= 1e-2, h
+        assert np.abs(o[0, h] - ref).max() <= 2e-2 * np.abs(ref).max(), h
+    assert (np.abs(l - rl) / np.maximum(np.abs(rl), 1.0)).max() <= 1e-3
+
+
+def _assert_close_bf16(o16, l, ro, rl, what):
+    """The gates of the fp32 result with the rounding of the result itself added: half a bf16 step,
+    2^-9 relative per element (2^-9 / sqrt(3) in the L2 norm)."""
+    o = o16.astype(np.float64)
+    assert np.isfinite(o).all() and np.isfinite(l).all(), what
+    diff = np.abs(o - ro)
+    half_ulp = np.abs(ro) * 2.0 ** -9
+    assert (diff <= 2e-2 + half_ulp).all(), what
+    assert diff.mean() <= 2e-3 + half_ulp.mean(), what
+    assert np.sqrt((diff ** 2).sum() / (ro ** 2).sum()) <= 1e-2 + 2.0 ** -9 / np.sqrt(3.0), what
+    assert (np.abs(l.astype(np.float64) - rl) / np.maximum(np.abs(rl), 1.0)).max() <= 1e-3, what
+
+
+@pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut", [(1, 24, 700, 3000, 3000, True),    # 72 tiles, every one cut in three
+                                                     (1, 4, 16384, 600, 570, False),   # 256 tiles: one full round, none cut
+                                                     (2, 5, 300, 2500, 2500, None)])
+def test_bf16_output_against_the_oracle(B, H, Sq, Skv, n_v, all_cut):
+    """pda_attn_fwd_bf16out element by element against the fp64 oracle (its cut tiles take their own
+    path: all parts go through the workspace and the merge pass writes bf16)."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    d = 128
+    if all_cut is not None:
+        plan = pda.attn_tail_plan(B, H, Sq, n_v, d)
+        if plan["n_tiles"] % torch.cuda.get_device_properties(0).multi_processor_count == 0:
+            assert plan["n_cut"] == 0 and not all_cut
+        else:
+            assert (plan["n_cut"] == plan["n_tiles"]) == all_cut
+    qb, kb, vb = gen_qkv(700 + H, B, H, Sq, Skv, d, unit_rms=True)
+    o16 = torch.full((B, H, Sq, d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    l16 = torch.full((B, H, Sq), float("nan"), device="cuda")
+    pda.attn_fwd_bf16out(to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), o16, l16, d ** -0.5, n_v)
+    torch.cuda.synchronize()
+    ro, rl = attention(qb, kb, vb, d ** -0.5, n_v)
+    _assert_close_bf16(o16.float().cpu().numpy(), l16.cpu().numpy(), ro, rl, f"bf16 out {(B, H, Sq, Skv, n_v)}")
 
 
 @pytest.mark.parametrize("B,H,Sq,Skv,n_v", [(1, 2, 515, 1100, 1050), (2, 5, 300, 2500, 2500), (1, 3, 5000, 5000, 4990),

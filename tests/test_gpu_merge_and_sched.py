@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from synth import CONFIGS, gen_qkv
-from tests.util import assert_close, gen_qkv_parallel, sample_rows, to_dev_bf16
+from tests.util import assert_close, cut_row_mask, gen_qkv_parallel, sample_rows, to_dev_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -38,16 +38,25 @@ def test_merge_matches_oracle_random_partials():
         assert np.array_equal(po[0].cpu().numpy(), o)
 
 
-def _assert_same_up_to_split(out, lse, ref_out, ref_lse):
-    """Two launches that cover the same rows with different grids agree bit for bit on every query
-    tile that both sweep in one pass; tiles of a launch's last, partly filled round of workgroups
-    are computed as key-range partials and merged, which rounds differently (at the level of the
-    bf16 rounding of P)."""
+def _n_cu():
     import torch
-    same = (out == ref_out).all(dim=-1)
-    assert same.float().mean().item() > 0.5                    # most rows are untouched by any split
-    assert ((out - ref_out).norm() / ref_out.norm()).item() < 5e-3
-    assert ((lse - ref_lse).abs() / ref_lse.abs().clamp(min=1)).max().item() < 1e-5
+    return torch.cuda.get_device_properties(0).multi_processor_count
+
+
+def _assert_same_except_cut_rows(out, lse, ref_out, ref_lse, cut):
+    """The paper's claim that chunked execution gives identical results (Experiments; Supplement,
+    visual comparison), made exact: two launches that cover the same rows with different grids
+    agree BIT FOR BIT on every row outside the query tiles that either launch computes as merged
+    key-range partials (`cut`: boolean [B,H,Sq], from the launch plans), and to the rounding of the
+    probabilities on those."""
+    import torch
+    cut = torch.from_numpy(cut).cuda()
+    assert 0 < int(cut.sum()) < cut.numel()                       # both kinds of rows are present
+    same = (out == ref_out).all(dim=-1) & (lse == ref_lse)
+    assert bool(same[~cut].all()), f"{int((~same[~cut]).sum())} uncut rows differ"
+    d_out, r_out = (out - ref_out)[cut], ref_out[cut]
+    assert (d_out.norm() / r_out.norm()).item() < 5e-3
+    assert ((lse - ref_lse).abs() / ref_lse.abs().clamp(min=1))[cut].max().item() < 1e-5
 
 
 def _fwd(q, k, v, scale, n_v=None, q_offset=0):
@@ -138,7 +147,13 @@ def test_c4_headchunk_720p():
     assert sum(gms) <= tms * 1.01 + 0.2                     # groups run back to back inside the total
     full, lfull = _fwd(q, k, v, w.scale)                     # one launch over all 24 heads
     torch.cuda.synchronize()
-    _assert_same_up_to_split(out, lse, full, lfull)
+    # rows cut by one of the eight 3-head launches or by the 24-head launch
+    n_cu = _n_cu()
+    cut = cut_row_mask(1, w.H, w.Sq, w.Skv, w.d, n_cu)[0]
+    for g in range(w.H // w.heads_per_group):
+        h0 = g * w.heads_per_group
+        cut[h0:h0 + w.heads_per_group] |= cut_row_mask(1, w.heads_per_group, w.Sq, w.Skv, w.d, n_cu)[0]
+    _assert_same_except_cut_rows(out, lse, full, lfull, cut[None])
     del full, lfull, sink
     for h in (0, 7, 13, 23):
         rows = sample_rows(w.Sq, 512, w.seed + h)
@@ -166,7 +181,11 @@ def test_c5_split_merge_720p():
         fo = torch.zeros_like(full); fl = torch.full_like(lfull, float("-inf"))
         fo[:, :, off:off + n] = o; fl[:, :, off:off + n] = l
         po.append(fo); pl.append(fl)
-    _assert_same_up_to_split(out_q, lse_q, full, lfull)
+    n_cu = _n_cu()
+    cut = cut_row_mask(1, w.H, w.Sq, w.Skv, w.d, n_cu)
+    for off, n in w.query_ranges:
+        cut[:, :, off:off + n] |= cut_row_mask(1, w.H, n, w.Skv, w.d, n_cu)
+    _assert_same_except_cut_rows(out_q, lse_q, full, lfull, cut)
     # the same three ranges as bench.py issues them: views of the full tensors, written in place
     out_s = torch.full_like(full, float("nan")); lse_s = torch.full_like(lfull, float("nan"))
     for off, n in w.query_ranges:
@@ -241,9 +260,8 @@ def test_strided_views_equal_compact_copies():
     pda.attn_merge(po, pl, mo, ml)
     torch.cuda.synchronize()
     assert ((mo - full).norm() / full.norm()).item() < 5e-3
-    # the normaliser is the sum of bf16-rounded weights: over chunks of only ~200 keys the two
-    # groupings differ at the 1e-4 level (the gate against the oracle is 1e-3)
-    assert ((ml - lfull).abs() / lfull.abs().clamp(min=1)).max().item() < 5e-4
+    # the normaliser is an fp32 sum of unrounded weights in both groupings
+    assert ((ml - lfull).abs() / lfull.abs().clamp(min=1)).max().item() < 1e-5
     # a head subset of a larger tensor (what a co-processing helper receives) with d = 64
     qb, kb, vb = gen_qkv(32, 1, 4, 300, 300, 64, unit_rms=False)
     q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)

@@ -1,43 +1,15 @@
 """Shared helpers of the GPU parity tests: upload of bf16 payloads, tolerances, row sampling."""
 from __future__ import annotations
 
-from concurrent.futures import ThreadPoolExecutor
-
 import numpy as np
 
-from synth import K_ID, Q_ID, V_ID, gen_tensor
+from synth import gen_qkv_parallel, to_dev_bf16  # noqa: F401  (re-exported for the tests)
 
 # Tolerances of the GPU path against the fp64 oracle on bf16 inputs with fp32 accumulation.
 MAX_ABS, MEAN_ABS, LSE_REL = 2e-2, 2e-3, 1e-3
 # Self-imposed on top: at long sequences outputs are O(sqrt(e/S)), so the absolute gates alone
 # would pass an all-zero result.  Relative L2 error over the compared rows.
 REL_L2 = 1e-2
-
-
-def to_dev_bf16(bits: np.ndarray):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
-
-
-def gen_qkv_parallel(w, heads=None, workers=8):
-    """q, k, v payloads of workload w (optionally a head range), generated head by head in threads."""
-    h0, h1 = heads if heads is not None else (0, w.H)
-    jobs = []
-    for tid, S in ((Q_ID, w.Sq), (K_ID, w.Skv), (V_ID, w.Skv)):
-        for h in range(h0, h1):
-            jobs.append((tid, S, h))
-
-    def run(job):
-        tid, S, h = job
-        return gen_tensor(w.seed, tid, (w.B, w.H, S, w.d), unit_rms=w.unit_rms, heads=(h, h + 1))
-
-    with ThreadPoolExecutor(max_workers=workers) as ex:
-        parts = list(ex.map(run, jobs))
-    n = h1 - h0
-    q = np.concatenate(parts[0:n], axis=1)
-    k = np.concatenate(parts[n:2 * n], axis=1)
-    v = np.concatenate(parts[2 * n:3 * n], axis=1)
-    return q, k, v
 
 
 def sample_rows(Sq: int, n: int, seed: int, tile: int = 256, extra=()):
@@ -74,3 +46,42 @@ def assert_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
     assert e["rel_l2"] <= REL_L2, msg
     assert e["lse_rel"] <= LSE_REL, msg
     return e
+
+
+def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
+    """Which query tiles a d = 128 attention launch computes as merged key-range partials: the rule
+    of pda_attn_tail_plan written out independently.  Tiles of 256 rows run one per compute unit
+    at a time; the n_tiles mod n_cu tiles of the last round are cut into s in {2, 3, 4} key ranges
+    when that lowers ceil(rem*s/n_cu)/s + 0.02*rem/n_cu below 1 (smallest cost, smallest s on
+    ties), a range holding at least 8 key tiles of 64."""
+    from fractions import Fraction
+    plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
+    if d != 128 or n_v <= 0 or BH * Sq <= 0:
+        return plan
+    tiles = -(-Sq // 256) * BH
+    plan["n_tiles"] = tiles
+    rem = tiles % n_cu
+    if rem == 0:
+        return plan
+    best, split = Fraction(1), 1
+    for s in (2, 3, 4):
+        if n_v < s * 512:
+            break
+        cost = Fraction(-(-rem * s // n_cu), s) + Fraction(2 * rem, 100 * n_cu)
+        if cost < best:
+            best, split = cost, s
+    if split > 1:
+        per = -(-n_v // split)
+        plan.update(n_cut=rem, split=split, part_keys=-(-per // 64) * 64, workspace_slots=rem * (split - 1))
+    return plan
+
+
+def cut_row_mask(B: int, H: int, Sq: int, n_v: int, d: int, n_cu: int):
+    """Boolean [B, H, Sq]: rows lying in a query tile that a launch over all B*H heads cuts."""
+    plan = tail_plan(B * H, Sq, n_v, d, n_cu)
+    mask = np.zeros((B * H, Sq), dtype=bool)
+    tph = -(-Sq // 256)
+    for t in range(plan["n_tiles"] - plan["n_cut"], plan["n_tiles"]):
+        bh, qt = divmod(t, tph)
+        mask[bh, qt * 256:(qt + 1) * 256] = True
+    return mask.reshape(B, H, Sq)
