@@ -101,6 +101,28 @@ int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out
                          float scale, int64_t kv_valid_len, int64_t q_offset, void* stream);
 
 /*
+ * pda_attn_fwd for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments, same arithmetic and the
+ * same work plan as pda_attn_fwd, but the key-range partials of cut query tiles (see
+ * pda_attn_tail_plan) go to a fixed buffer inside the library instead of the stream's workspace,
+ * and the call allocates, frees and synchronises nothing.  (Its first call on a device looks up
+ * the buffer's address, once; a caller that captures graphs makes one call before capturing.)
+ * The buffer is a device array of PDA_NOALLOC_SCRATCH_BYTES bytes (PDA_NOALLOC_MAX_SLOTS partial
+ * slots of 132 096 bytes) that every GPU the library runs on holds from the time the library is
+ * loaded until the process ends.  A launch whose plan needs more slots than that returns
+ * PDA_ERR_UNSUPPORTED and launches nothing (with 256 compute units no fp32-output launch needs
+ * more than 576 slots, so nothing is rejected there).  All calls on one GPU share the one buffer,
+ * whatever their stream: calls whose execution may overlap on a GPU race on it and must be
+ * ordered by the caller (one stream, or events).  Nothing in it needs to start at zero: every
+ * slot a launch reads was written by the same launch first.
+ */
+#define PDA_NOALLOC_MAX_SLOTS 576
+#define PDA_NOALLOC_SCRATCH_BYTES 76087296 /* 576 * (256*128 + 256) * 4 */
+int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, int64_t q_offset, void* stream);
+
+/*
  * How a d = 128 attention launch over B*H (batch, head) pairs is cut into work items (host only;
  * every pointer below is a HOST pointer; no device work).  The kernel takes 256-row query tiles,
  * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles

@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libpipedit_attn.so")
 
 PDA_OK, PDA_ERR_INVALID_ARG, PDA_ERR_UNSUPPORTED, PDA_ERR_HIP, PDA_ERR_NOMEM = 0, 1, 2, 3, 4
 PDA_MAX_PARTIALS = 16
+PDA_NOALLOC_MAX_SLOTS = 576
 PDA_MAX_LOCAL_HEADS = 64
 PDA_SINK_HEAD_MAJOR, PDA_SINK_TOKEN_ARRIVAL, PDA_SINK_TOKEN_FINAL = 0, 1, 2
 
@@ -39,6 +40,8 @@ def _load() -> C.CDLL:
     lib.pda_attn_fwd.restype = i32
     lib.pda_attn_fwd_strided.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32] + [i64] * 8 + [f32, i64, i64, vp]
     lib.pda_attn_fwd_strided.restype = i32
+    lib.pda_attn_fwd_noalloc.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i64, vp]
+    lib.pda_attn_fwd_noalloc.restype = i32
     lib.pda_attn_fwd_variant.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i32, vp]
     lib.pda_attn_fwd_variant.restype = i32
     lib.pda_attn_tail_plan.argtypes = [i32, i32, i64, i64, i32, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32),
@@ -126,6 +129,22 @@ def attn_fwd(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None
     n_v = Skv if kv_valid_len is None else int(kv_valid_len)
     _check(lib.pda_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
                             n_v, int(q_offset), _stream_handle(stream)))
+    return out, lse
+
+
+def attn_fwd_noalloc(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None, q_offset: int = 0, stream=None):
+    """pda_attn_fwd_noalloc: attn_fwd with the partials of cut tiles in the library's static device buffer."""
+    import torch
+    B, H, Sq, d = q.shape
+    Skv = k.shape[2]
+    _expect(q, torch.bfloat16, (B, H, Sq, d), "q")
+    _expect(k, torch.bfloat16, (B, H, Skv, d), "k")
+    _expect(v, torch.bfloat16, (B, H, Skv, d), "v")
+    _expect(out, torch.float32, (B, H, Sq, d), "out")
+    _expect(lse, torch.float32, (B, H, Sq), "lse")
+    n_v = Skv if kv_valid_len is None else int(kv_valid_len)
+    _check(lib.pda_attn_fwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, Sq, Skv, d, float(scale),
+                                    n_v, int(q_offset), _stream_handle(stream)))
     return out, lse
 
 

@@ -141,7 +141,34 @@ int cached_workspace(hipStream_t st, int64_t need_slots, CachedWs* out) {
     return PDA_OK;
 }
 
-enum WsKind { WS_CACHED };
+// (2) Static: for callers that cannot allocate (pda_attn_fwd_noalloc).  A file-scope device array;
+// every GPU the library runs on holds its own copy at its own address, looked up once per device.
+// In host code the array's NAME is not a device address: only the pointer hipGetSymbolAddress
+// returns is ever handed to a kernel.
+constexpr int64_t kStaticSlots = PDA_NOALLOC_MAX_SLOTS;
+static __device__ __align__(256) float scratch[kStaticSlots * pda::kSlotFloats];
+static_assert(sizeof(float) * kStaticSlots * pda::kSlotFloats == PDA_NOALLOC_SCRATCH_BYTES, "header and library disagree");
+
+int static_workspace(float** out) {
+    static std::mutex mu;
+    static float* per_dev[pda::KernelSetup::MAX_DEV] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "device query");
+    if (dev < 0 || dev >= pda::KernelSetup::MAX_DEV) return fail(PDA_ERR_UNSUPPORTED, "device index %d beyond %d", dev, pda::KernelSetup::MAX_DEV);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_dev[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return fail(PDA_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+        per_dev[dev] = static_cast<float*>(ptr);
+    }
+    *out = per_dev[dev];
+    return PDA_OK;
+}
+
+enum WsKind { WS_CACHED, WS_STATIC };
 
 // Validated attention launch for hg heads of B batches with the workspace the launch needs.
 int launch_checked(const void* q, const void* k, const void* v, float* out, float* lse,
@@ -156,11 +183,21 @@ int launch_checked(const void* q, const void* k, const void* v, float* out, floa
         if (e != hipSuccess) return hip_fail(e, "device query");
         const int64_t need = pda::tail_slots(pda::plan_tail(Sq, B * hg, n_v, n_cu), out_bf16);
         if (need > 0) {
-            CachedWs w{};
-            int rc = cached_workspace(st, need, &w);
-            if (rc != PDA_OK) return rc;
-            ws = w.ptr;
-            ws_slots = w.slots;
+            if (kind == WS_STATIC) {
+                if (need > kStaticSlots)
+                    return fail(PDA_ERR_UNSUPPORTED, "this launch needs %lld partial slots (%lld bytes) of scratch; the static buffer holds %lld (%lld bytes)",
+                                (long long)need, (long long)(need * pda::kSlotFloats * sizeof(float)),
+                                (long long)kStaticSlots, (long long)PDA_NOALLOC_SCRATCH_BYTES);
+                int rc = static_workspace(&ws);
+                if (rc != PDA_OK) return rc;
+                ws_slots = kStaticSlots;
+            } else {
+                CachedWs w{};
+                int rc = cached_workspace(st, need, &w);
+                if (rc != PDA_OK) return rc;
+                ws = w.ptr;
+                ws_slots = w.slots;
+            }
         }
     }
     hipError_t e = launch_strided(q, k, v, out, lse, B, hg, Sq, d, s, scale, n_v, st, variant, base2, out_bf16, ws, ws_slots);
@@ -288,6 +325,17 @@ int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float*
     if (q_offset < 0) return fail(PDA_ERR_INVALID_ARG, "q_offset=%lld is negative", (long long)q_offset);
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
     return launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H, static_cast<hipStream_t>(stream));
+}
+
+int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out, float* lse,
+                         int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
+                         int64_t kv_valid_len, int64_t q_offset, void* stream) {
+    int rc = check_attn_args(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len);
+    if (rc != PDA_OK) return rc;
+    if (q_offset < 0) return fail(PDA_ERR_INVALID_ARG, "q_offset=%lld is negative", (long long)q_offset);
+    if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
+    return launch_heads(q, k, v, out, lse, B, H, Sq, Skv, d, scale, kv_valid_len, 0, H, static_cast<hipStream_t>(stream),
+                        0, WS_STATIC);
 }
 
 int pda_attn_fwd_variant(const void* q, const void* k, const void* v, float* out, float* lse,

@@ -23,7 +23,7 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(pda):
     names = _declared_symbols()
-    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_bf16out", "pda_attn_fwd_strided",
+    assert names == ["pda_attn_fwd", "pda_attn_fwd_base2", "pda_attn_fwd_bf16out", "pda_attn_fwd_noalloc", "pda_attn_fwd_strided",
                      "pda_attn_fwd_variant", "pda_attn_merge", "pda_attn_tail_plan",
                      "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
