@@ -15,8 +15,16 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Wno-inline-asm"]      # the DMA helpers declare m0, a register the compiler reserves, as clobbered
 
 
-def build_library(verbose: bool = False) -> str:
-    cmd = [HIPCC, *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def build_library(verbose: bool = False, host_sanitizers: bool = False) -> str:
+    """Compile the library next to this file.  host_sanitizers: build the HOST side (argument
+    validation, planner, scheduler) with AddressSanitizer and UndefinedBehaviorSanitizer for a CPU
+    test run (load it with the ASan runtime preloaded); device code is built as usual."""
+    flags = list(FLAGS)
+    if host_sanitizers:
+        flags = [f for f in flags if f != "-O3"] + ["-O1", "-g", "-Xarch_host", "-fsanitize=address",
+                                                      "-Xarch_host", "-fsanitize=undefined",
+                                                      "-Xarch_host", "-fno-omit-frame-pointer"]
+    cmd = [HIPCC, *flags, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
