@@ -15,103 +15,137 @@
 
 namespace pda {
 
-static unsigned grid_1d(int64_t items, int64_t cap = 256 * 32) {
-    int64_t blocks = (items + 255) / 256;
-    return (unsigned)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
+// Launch shape of the streaming kernels here.  One item per thread, workgroups dispatched in
+// address order: a grid of exactly as many workgroups as there are items streams through HBM
+// measurably faster than a capped grid whose workgroups stride over the data.  Long axes (rows,
+// tokens) are spread over grid.y and grid.z so that no thread divides a 64-bit index (a 64-bit
+// division costs about a hundred instructions per thread, more than the copy itself).
+struct RowGrid {
+    unsigned y, z;
+};
+static RowGrid row_grid(int64_t rows) {
+    const int64_t y = rows < 65535 ? (rows > 0 ? rows : 1) : 65535;
+    return {(unsigned)y, (unsigned)((rows + y - 1) / y)};     // up to 65535^2 rows
+}
+__device__ __forceinline__ int64_t grid_row() { return (int64_t)blockIdx.z * gridDim.y + blockIdx.y; }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xF, 0xF, false));
 }
 
-// blockIdx.y = local head j (so the chunk pointer is wave-uniform and comes from the kernel
-// arguments); blockIdx.x strides over the (row, source GPU i, 4-column) items of that chunk.
+// Algorithm 1 steps 10-13.  grid.y/z = row r; grid.x covers the row's h*n*D/4 float4s in INPUT
+// order of the concatenated tensor (local head j, source GPU i, 4 columns): consecutive
+// workgroups read consecutive memory when the chunks are the slices of one concatenated
+// [rows, h*n, D] tensor (h sequential streams when they are separate tensors) and write inside
+// the same hidden row.  The chunk pointers are read from the kernel arguments with a per-lane
+// index (uniform over a wavefront whenever n*D/4 is a multiple of 64).
 __global__ __launch_bounds__(256) void postprocess_kernel(const PostParams p) {
-    const int j = blockIdx.y;
+    const int64_t r = grid_row();
+    const unsigned per_row = (unsigned)p.n * p.D4;           // float4s of one chunk row
+    const unsigned out_row = per_row * p.h;                  // float4s of one hidden row
+    const unsigned t = blockIdx.x * 256u + threadIdx.x;
+    if (r >= p.rows || t >= out_row) return;
+    const unsigned j = t / per_row;
+    const unsigned rem = t - j * per_row;
+    const unsigned i = rem / (unsigned)p.D4;
+    const unsigned c = rem - i * p.D4;
     const float4* __restrict__ src = reinterpret_cast<const float4*>(p.chunk[j]);
     float4* __restrict__ dst = reinterpret_cast<float4*>(p.hidden);
-    const int64_t per_row = (int64_t)p.n * p.D4;             // float4s of one chunk row
-    const int64_t total = p.rows * per_row;
-    const int64_t out_row = per_row * p.h;                   // float4s of one hidden row
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t r = t / per_row;
-        const int rem = (int)(t - r * per_row);
-        const int i = rem / p.D4;
-        const int c = rem - i * p.D4;
-        nt_store4(dst + r * out_row + (int64_t)(i * p.h + j) * p.D4 + c, nt_load4(src + r * p.row_stride4 + rem));
-    }
+    nt_store4(dst + r * out_row + (i * p.h + j) * p.D4 + c, nt_load4(src + r * p.row_stride4 + rem));
 }
 
 hipError_t launch_postprocess(const PostParams& p, hipStream_t st) {
-    const int64_t per_chunk = p.rows * p.n * p.D4;
-    const unsigned gx = grid_1d(per_chunk, (256 * 32 + p.h - 1) / p.h);
-    hipLaunchKernelGGL(postprocess_kernel, dim3(gx, p.h), dim3(256), 0, st, p);
+    const RowGrid g = row_grid(p.rows);
+    const unsigned out_row = (unsigned)p.n * p.D4 * p.h;
+    hipLaunchKernelGGL(postprocess_kernel, dim3((out_row + 255) / 256, g.y, g.z), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
 // src: hg heads of one batch, [hg, S, d] contiguous (heads h0 .. h0+hg-1 of the full H = n*h);
-// dst: that batch's [S, H, d].
+// dst: that batch's [S, H, d].  grid.y/z = block of TOK tokens; grid.x covers the block's
+// TOK*hg*d/4 float4s in OUTPUT order (token, head of the group, 4 columns): the group's heads of
+// one token are written next to each other where their slots are adjacent; reads are hg
+// sequential streams.
+constexpr int SCATTER_TOK = 64;
 __global__ __launch_bounds__(256) void scatter_heads_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
                                                             int64_t S, int d4, int hg, int H, int h0, int h, int n,
                                                             int arrival) {
-    const int64_t per_head = S * d4;
-    const int64_t total = per_head * hg;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
-        const int jj = (int)(t / per_head);
-        const int64_t rem = t - (int64_t)jj * per_head;
-        const int64_t s = rem / d4;
-        const int c = (int)(rem - s * d4);
-        const int k = h0 + jj;                               // global head = i*h + j
-        const int slot = arrival ? (k % h) * n + k / h : k;  // k_mod(i,j) = j*n + i, or k_orig
-        nt_store4(dst + (s * H + slot) * d4 + c, nt_load4(src + t));
-    }
+    const unsigned per_tok = (unsigned)hg * d4;
+    const unsigned t = blockIdx.x * 256u + threadIdx.x;
+    const unsigned tok = t / per_tok;
+    const int64_t s = grid_row() * SCATTER_TOK + tok;
+    if (tok >= SCATTER_TOK || s >= S) return;
+    const unsigned rem = t - tok * per_tok;
+    const unsigned jj = rem / (unsigned)d4;
+    const unsigned c = rem - jj * d4;
+    const int k = h0 + (int)jj;                              // global head = i*h + j
+    const int slot = arrival ? (k % h) * n + k / h : k;      // k_mod(i,j) = j*n + i, or k_orig
+    nt_store4(dst + (s * H + slot) * d4 + c, nt_load4(src + (int64_t)jj * S * d4 + s * d4 + c));
 }
 
 hipError_t launch_scatter_heads(const float* src, float* dst, int64_t S, int d, int hg, int H, int h0,
                                 int h, int n, int arrival, hipStream_t st) {
-    hipLaunchKernelGGL(scatter_heads_kernel, dim3(grid_1d((int64_t)hg * S * (d / 4))), dim3(256), 0, st,
+    const RowGrid g = row_grid((S + SCATTER_TOK - 1) / SCATTER_TOK);
+    const unsigned items = (unsigned)SCATTER_TOK * hg * (d / 4);
+    hipLaunchKernelGGL(scatter_heads_kernel, dim3((items + 255) / 256, g.y, g.z), dim3(256), 0, st,
                        reinterpret_cast<const float4*>(src), reinterpret_cast<float4*>(dst), S, d / 4, hg, H, h0, h, n, arrival);
     return hipGetLastError();
 }
 
-// LPV = lanes per d-vector (d/4: 16 or 32).  Items are ordered by OUTPUT position, so the bf16
-// writes are contiguous and the fp32 reads are d-float segments H*d floats apart.
+// LPV = lanes per d-vector (d/4: 16 or 32).  A workgroup packs VPB consecutive tokens of one head:
+// it reads VPB d-float segments (H*d floats apart) and writes VPB*d contiguous bf16.
+// grid.x = head, grid.y/z = (batch, token block): the H workgroups of one token block, dispatched
+// one after the other, together read one contiguous piece of x, and every head's output advances
+// sequentially.
 template <int LPV>
 __global__ __launch_bounds__(256) void pack_heads_kernel(const float4* __restrict__ x, uint2* __restrict__ y,
-                                                         int64_t S, int H, int64_t n_vec /* B*H*S */, int unit_rms, float premul) {
-    constexpr int VPB = 256 / LPV;                            // vectors per workgroup pass
+                                                         int64_t S, int H, int64_t n_blk /* ceil(S/VPB) */, int B,
+                                                         int unit_rms, float premul) {
+    constexpr int VPB = 256 / LPV;                            // tokens per workgroup
     const int lane = threadIdx.x % LPV;
-    const int64_t n_pass = (n_vec + VPB - 1) / VPB;
-    for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
-        const int64_t o = pass * VPB + threadIdx.x / LPV;     // output vector index (b*H + h)*S + s
-        const bool live = o < n_vec;
-        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (live) {
-            const int64_t bh = o / S;
-            const int64_t s = o - bh * S;
-            const int64_t b = bh / H;
-            const int hh = (int)(bh - b * H);
-            a = nt_load4(x + ((b * S + s) * H + hh) * LPV + lane);
+    const int hh = blockIdx.x;
+    const int64_t bb = grid_row();                            // b * n_blk + block
+    if (bb >= n_blk * B) return;
+    int64_t b = 0, blk = bb;
+    if (B > 1) { b = bb / n_blk; blk = bb - b * n_blk; }     // wave-uniform, taken only with several batches
+    const int64_t s = blk * VPB + threadIdx.x / LPV;
+    const bool live = s < S;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) a = nt_load4(x + ((b * S + s) * H + hh) * LPV + lane);
+    if (unit_rms) {
+        // sum of squares over the vector's LPV lanes, in registers (DPP lane permutations and, for
+        // 32 lanes, the 16-lane row swap): every lane ends up with the total
+        float ss = a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        ss += dpp_f32<0xB1>(ss);          // quad_perm [1,0,3,2]: lane ^ 1
+        ss += dpp_f32<0x4E>(ss);          // quad_perm [2,3,0,1]: lane ^ 2
+        ss += dpp_f32<0x141>(ss);         // row_half_mirror: the other quad of each 8
+        ss += dpp_f32<0x140>(ss);         // row_mirror: the other half of each 16
+        if constexpr (LPV == 32) {
+            auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(ss), __float_as_uint(ss), false, false);
+            ss = __uint_as_float(r[0]) + __uint_as_float(r[1]);    // lane ^ 16
         }
-        if (unit_rms) {
-            float ss = a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
-#pragma unroll
-            for (int m = 1; m < LPV; m <<= 1) ss += __shfl_xor(ss, m, LPV);
-            const float inv = ss > 0.f ? premul / sqrtf(ss * (1.0f / (4 * LPV))) : 0.f;
-            a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
-        } else if (premul != 1.0f) {
-            a.x *= premul; a.y *= premul; a.z *= premul; a.w *= premul;
-        }
-        if (live) {
-            nt_store2(y + o * LPV + lane, pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));   // round to nearest even
-        }
+        // 1/sqrt by the hardware approximation (1 ulp): far inside the bf16 rounding that follows
+        const float inv = ss > 0.f ? premul * __builtin_amdgcn_rsqf(ss * (1.0f / (4 * LPV))) : 0.f;
+        a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+    } else if (premul != 1.0f) {
+        a.x *= premul; a.y *= premul; a.z *= premul; a.w *= premul;
+    }
+    if (live) {
+        nt_store2(y + ((b * H + hh) * S + s) * LPV + lane, pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));   // round to nearest even
     }
 }
 
 hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, float premul, hipStream_t st) {
-    const int64_t n_vec = (int64_t)B * H * S;
     const float4* xs = reinterpret_cast<const float4*>(x);
     uint2* yd = reinterpret_cast<uint2*>(y);
+    const int vpb = d == 128 ? 8 : 16;
+    const int64_t n_blk = (S + vpb - 1) / vpb;
+    const RowGrid g = row_grid(n_blk * B);
     if (d == 128) {
-        hipLaunchKernelGGL(pack_heads_kernel<32>, dim3(grid_1d(n_vec * 32)), dim3(256), 0, st, xs, yd, S, H, n_vec, unit_rms, premul);
+        hipLaunchKernelGGL(pack_heads_kernel<32>, dim3(H, g.y, g.z), dim3(256), 0, st, xs, yd, S, H, n_blk, B, unit_rms, premul);
     } else {
-        hipLaunchKernelGGL(pack_heads_kernel<16>, dim3(grid_1d(n_vec * 16)), dim3(256), 0, st, xs, yd, S, H, n_vec, unit_rms, premul);
+        hipLaunchKernelGGL(pack_heads_kernel<16>, dim3(H, g.y, g.z), dim3(256), 0, st, xs, yd, S, H, n_blk, B, unit_rms, premul);
     }
     return hipGetLastError();
 }
