@@ -391,6 +391,16 @@ def main():
     res["roofline"]["mfma_only_same_data"] = {"achieved": probe_tf, "unit": "TFLOP/s", "ms": probe_ms,
                                               "what": "loop of bf16 32x32x16 MFMAs only, operands = values of Q, 2 wavefronts per SIMD"}
     res["roofline"]["frac_of_mfma_only"] = achieved / probe_tf
+    # what the other instruction classes of the kernel's loop cost on this data under the power limit:
+    # the same MFMA loop with them added one after the other at the kernel's density (no DMA, no barriers)
+    ladder = {}
+    for mix, name in ((1, "plus_softmax_arithmetic"), (2, "plus_operand_reads_from_lds"), (3, "with_half_the_operand_reads")):
+        tf, _ = pda.probe_loop_rate(q, mix, 1 << 19, stream=cs)
+        ladder[name] = tf
+    res["roofline"]["loop_budget"] = {"unit": "TFLOP/s", "mfma_only": probe_tf, **ladder, "attention_launch": achieved,
+                                      "frac_of_loop_with_reads": achieved / ladder["plus_operand_reads_from_lds"],
+                                      "what": "MFMA-only loop on Q's values, then with the softmax arithmetic and the LDS operand "
+                                              "reads of the attention loop added at the kernel's density (pda_probe_loop_rate)"}
     if not args.no_next_rows:
         del qr, kc, kc_out, outq, lseq
         res["next_rows"] = next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, args.t_linear_ms)

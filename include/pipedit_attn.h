@@ -322,6 +322,22 @@ int pda_plan_ragged_groups(int H, int n, int* group_sizes);
 int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave,
                         float* tflops, float* ms, void* stream);
 
+/*
+ * pda_probe_mfma_rate with the other instruction classes of the attention kernel's inner loop
+ * added to the MFMA loop at the kernel's own density, so that what each class costs under the
+ * chip's power limit can be measured on the caller's data, one class after the other:
+ *   mix 0: MFMAs only (pda_probe_mfma_rate)
+ *   mix 1: + the softmax arithmetic: per MFMA one fp32 multiply-add, one exponential, one add
+ *          and half a conversion to bf16
+ *   mix 2: + the MFMA operand fragments read from LDS as the kernel reads them: per two MFMAs
+ *          one 16-byte read and one pair of transposing 8-byte reads per lane
+ *   mix 3: mix 2 with half the reads (what a wavefront owning 64 instead of 32 query rows needs)
+ * No global->LDS copies, no barriers, no dependencies between the classes: an upper bound for the
+ * kernel's steady state.  Arguments and conventions as pda_probe_mfma_rate; SYNCHRONOUS.
+ */
+int pda_probe_loop_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave, int mix,
+                        float* tflops, float* ms, void* stream);
+
 /* Message of the calling thread's most recent failure ("" if none). Never NULL. */
 const char* pda_last_error(void);
 

@@ -74,6 +74,8 @@ def _load() -> C.CDLL:
     lib.pda_plan_ragged_groups.restype = i32
     lib.pda_probe_mfma_rate.argtypes = [vp, i64, i64, C.POINTER(f32), C.POINTER(f32), vp]
     lib.pda_probe_mfma_rate.restype = i32
+    lib.pda_probe_loop_rate.argtypes = [vp, i64, i64, i32, C.POINTER(f32), C.POINTER(f32), vp]
+    lib.pda_probe_loop_rate.restype = i32
     lib.pda_last_error.argtypes = []
     lib.pda_last_error.restype = C.c_char_p
     lib.pda_version.argtypes = []
@@ -384,5 +386,16 @@ def probe_mfma_rate(operands, mfma_per_wave: int = 1 << 20, stream=None):
         raise ValueError("operands: expected a contiguous cuda bf16 tensor")
     tf, ms = C.c_float(0.0), C.c_float(0.0)
     _check(lib.pda_probe_mfma_rate(_ptr(operands), operands.numel(), int(mfma_per_wave), C.byref(tf), C.byref(ms),
+                                   _stream_handle(stream)))
+    return tf.value, ms.value
+
+
+def probe_loop_rate(operands, mix: int, mfma_per_wave: int = 1 << 20, stream=None):
+    """pda_probe_loop_rate: (TFLOP/s, ms) of the MFMA loop with the attention loop's other instruction classes (mix 0..3)."""
+    import torch
+    if operands.dtype != torch.bfloat16 or not operands.is_contiguous() or not operands.is_cuda:
+        raise ValueError("operands: expected a contiguous cuda bf16 tensor")
+    tf, ms = C.c_float(0.0), C.c_float(0.0)
+    _check(lib.pda_probe_loop_rate(_ptr(operands), operands.numel(), int(mfma_per_wave), int(mix), C.byref(tf), C.byref(ms),
                                    _stream_handle(stream)))
     return tf.value, ms.value

@@ -534,16 +534,16 @@ int pda_pack_heads(const float* x, void* y, int B, int64_t S, int H, int d, int 
     return PDA_OK;
 }
 
-int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave,
-                        float* tflops, float* ms, void* stream) {
+static int probe_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave, int mix,
+                      float* tflops, float* ms, void* stream) {
     if (!operands || !tflops) return fail(PDA_ERR_INVALID_ARG, "null operands/tflops");
     if (n_elems < 4096) return fail(PDA_ERR_INVALID_ARG, "n_elems=%lld (need >= 4096)", (long long)n_elems);
     if (mfma_per_wave < 1 || mfma_per_wave > ((int64_t)1 << 32)) return fail(PDA_ERR_INVALID_ARG, "mfma_per_wave out of range");
+    if (mix < 0 || mix > 3) return fail(PDA_ERR_INVALID_ARG, "mix=%d (0..3)", mix);
     if (!aligned16(operands)) return fail(PDA_ERR_UNSUPPORTED, "operands must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int dev = 0, n_cu = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    int n_cu = 0;
+    hipError_t e = pda::device_cu_count(&n_cu);
     if (e != hipSuccess) return hip_fail(e, "device query");
     CachedWs w{};
     int rc = cached_workspace(st, 1, &w);            // one slot is far more than the 512 floats needed
@@ -552,10 +552,10 @@ int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (e == hipSuccess) e = hipEventCreate(&e0);
     if (e == hipSuccess) e = hipEventCreate(&e1);
-    const int64_t iters = (mfma_per_wave + 7) / 8;
+    const int64_t iters = (mfma_per_wave + 15) / 16 * 2;       // units of 8 MFMAs, an even number of them
     float t = 0.f;
     if (e == hipSuccess) e = hipEventRecord(e0, st);
-    if (e == hipSuccess) e = pda::launch_mfma_rate(operands, n_elems / 8, iters, n_cu, sink, st);
+    if (e == hipSuccess) e = pda::launch_mfma_rate(operands, n_elems / 8, iters, n_cu, mix, sink, st);
     if (e == hipSuccess) e = hipEventRecord(e1, st);
     if (e == hipSuccess) e = hipEventSynchronize(e1);
     if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
@@ -566,6 +566,16 @@ int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_
     *tflops = (float)(flop / ((double)t * 1e-3) * 1e-12);
     if (ms) *ms = t;
     return PDA_OK;
+}
+
+int pda_probe_mfma_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave,
+                        float* tflops, float* ms, void* stream) {
+    return probe_rate(operands, n_elems, mfma_per_wave, 0, tflops, ms, stream);
+}
+
+int pda_probe_loop_rate(const void* operands, int64_t n_elems, int64_t mfma_per_wave, int mix,
+                        float* tflops, float* ms, void* stream) {
+    return probe_rate(operands, n_elems, mfma_per_wave, mix, tflops, ms, stream);
 }
 
 int pda_plan_n_decode(double t_denoise, double t_decode, int N, int* n_decode) {

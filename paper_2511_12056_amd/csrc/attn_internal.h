@@ -163,8 +163,9 @@ hipError_t launch_scatter_heads(const float* src, float* dst, int64_t S, int d, 
 // every element times premul before the rounding.
 hipError_t launch_pack(const float* x, void* y, int B, int64_t S, int H, int d, int unit_rms, float premul, hipStream_t st);
 
-// MFMA-only loop (probe.hip): n_cu workgroups x 8 wavefronts, each wavefront issues 8*iters MFMAs
-// (32x32x16 bf16) on fragments read from src (n_frag 16-byte fragments); sink: >= 512 floats.
-hipError_t launch_mfma_rate(const void* src, int64_t n_frag, int64_t iters, int n_cu, float* sink, hipStream_t st);
+// MFMA rate probes (probe.hip): n_cu workgroups x 8 wavefronts, each wavefront issues about 8*iters
+// MFMAs (32x32x16 bf16) on fragments read from src (n_frag 16-byte fragments); mix 0 = MFMAs only,
+// 1..3 = with the other instruction classes of the attention loop added; sink: >= 512 floats.
+hipError_t launch_mfma_rate(const void* src, int64_t n_frag, int64_t iters, int n_cu, int mix, float* sink, hipStream_t st);
 
 }  // namespace pda

@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(pda):
                      "pda_attn_fwd_variant", "pda_attn_merge", "pda_attn_tail_plan",
                      "pda_headchunk_run", "pda_headchunk_run_ex", "pda_last_error",
                      "pda_pack_heads", "pda_pipesp_postprocess", "pda_plan_aco", "pda_plan_head_padding",
-                     "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_mfma_rate", "pda_version"]
+                     "pda_plan_n_decode", "pda_plan_ragged_groups", "pda_probe_loop_rate", "pda_probe_mfma_rate", "pda_version"]
     lib = C.CDLL(pda.lib_path())
     for n in names:
         assert getattr(lib, n) is not None
@@ -167,6 +167,10 @@ def test_probe_rejects_bad_arguments(pda):
     assert f(64, 8192, 0, C.byref(out), None, None) == 1
     assert f(64, 8192, 1000, None, None, None) == 1
     assert f(72, 8192, 1000, C.byref(out), None, None) == 2
+    g = pda.lib.pda_probe_loop_rate
+    assert g(64, 8192, 1000, 4, C.byref(out), None, None) == 1 and "mix" in pda.last_error()
+    assert g(64, 8192, 1000, -1, C.byref(out), None, None) == 1
+    assert g(None, 8192, 1000, 1, C.byref(out), None, None) == 1
 
 
 def test_attn_fwd_strided_rejects_bad_arguments(pda):
