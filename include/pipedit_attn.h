@@ -6,7 +6,7 @@
  * per (device, stream) for the key-range partials of the d = 128 attention
  * kernel (see pda_attn_tail_plan).  It is allocated once, the first time a
  * launch on that stream needs one, with the largest size any launch can need
- * on that device (768 slots of 132 096 bytes = 101 MB with 256 compute units);
+ * on that device (831 slots of 132 096 bytes = 110 MB with 256 compute units);
  * it never grows and is kept until the process ends, so after that first call
  * per stream the attention entry points neither allocate nor free nor
  * synchronise.  Work enqueued on one stream shares that stream's workspace,
@@ -127,13 +127,13 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
  * every pointer below is a HOST pointer; no device work).  The kernel takes 256-row query tiles,
  * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles
  * (in (batch, head, query tile) order: the partly filled last round) are each computed as `split`
- * partial attentions over key ranges of part_keys keys and merged with the formula of
+ * (2..16) partial attentions over key ranges of part_keys keys and merged with the formula of
  * pda_attn_merge; all other tiles are swept in one pass.  Hence two launches agree bit for bit
  * on every row that lies in an uncut tile of both, and to the rounding of the probabilities on
  * the others.  n_cu: compute units of the device (0 = ask the current device).  Outputs (any may
  * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_keys, and
- * workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32 out).
- * d = 64 launches and empty key sets are never cut.
+ * workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32 out; never more
+ * than 9/4 per compute unit).  d = 64 launches and empty key sets are never cut.
  */
 int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
                        int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_keys, int64_t* workspace_slots);

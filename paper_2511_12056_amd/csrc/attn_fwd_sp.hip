@@ -593,10 +593,12 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     // fp32 out: part 0 sits in out/lse and parts 1.. in the workspace; bf16 out: all parts in the workspace
     const int n_ws = p.out_bf16 ? p.split : p.split - 1;
     const int64_t slot0 = (int64_t)(tile - p.n_full) * n_ws;
-    float l[4];
-    float4 x[4];
+    float l[kMaxSplit];
+    float4 x[kMaxSplit];
     float m = -INFINITY;
-    for (int j = 0; j < p.split; ++j) {
+#pragma unroll
+    for (int j = 0; j < kMaxSplit; ++j) {
+        if (j >= p.split) break;
         if (j == 0 && !p.out_bf16) {
             l[0] = *lp;
             x[0] = reinterpret_cast<const float4*>(p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D)[c4];
@@ -609,7 +611,9 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     }
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float tot = 0.f;
-    for (int j = 0; j < p.split; ++j) {
+#pragma unroll
+    for (int j = 0; j < kMaxSplit; ++j) {
+        if (j >= p.split) break;
         const float w = __expf(l[j] - m);
         acc.x += w * x[j].x; acc.y += w * x[j].y; acc.z += w * x[j].z; acc.w += w * x[j].w;
         tot += w;

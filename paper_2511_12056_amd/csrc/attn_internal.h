@@ -64,13 +64,18 @@ struct AttnParams {
 };
 
 // Tail plan of the software-pipelined kernel (d = 128, 256-row query tiles, one workgroup per CU
-// at a time, so tiles run in rounds of n_cu).  The tiles of the last, partly filled round are cut
-// into `split` key ranges (2..4, each at least 8 key tiles long) so that the tail is made of
-// shorter items; they may spill over one round of such items.  Cost of the tail in tile-times:
-// ceil(rem * split / n_cu) / split, plus a small charge per cut tile for the partial stores and
-// the merge pass (cutting tiles of earlier, full rounds as well never lowers that cost).
+// at a time, so tiles run in rounds of n_cu).  The `rem` tiles of the last, partly filled round
+// are cut into `split` key ranges (2..16, each at least 8 key tiles long) so that the tail is made
+// of shorter items, run in ceil(rem * split / n_cu) rounds.  Cost of the tail in units of one
+// whole-tile sweep of nt key tiles:
+//     rounds * (1 / split + 4 / nt)  +  0.02 * rem / n_cu
+// (every item pays about four key-tile times for its prologue and its partial store; the last
+// term stands for the merge pass), against 1 for an uncut last round; the smallest cost wins,
+// the smaller split on ties.  The parts beyond the first of all cut tiles must fit the workspace:
+// rem * (split - 1) <= 9 * n_cu / 4.  (Cutting tiles of earlier, full rounds never pays.)
 // A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
 // the last n_cut of the launch's n_tiles tiles in (batch, head, query tile) order.
+constexpr int kMaxSplit = 16;
 struct TailPlan {
     int tiles_per_head;
     int64_t n_tiles;
@@ -78,17 +83,20 @@ struct TailPlan {
     int split;              // 1 if no tile is cut
     int64_t part_keys;      // keys per range (multiple of 64); 0 if no tile is cut
 };
+inline int64_t max_extra_slots(int n_cu) { return (int64_t)n_cu * 9 / 4; }
 inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
     TailPlan t{};
     t.tiles_per_head = (int)((Sq + 255) / 256);
     t.n_tiles = (int64_t)t.tiles_per_head * BH;
     t.split = 1;
-    const int rem = (int)(t.n_tiles % n_cu);
+    const int64_t rem = t.n_tiles % n_cu;
     if (rem) {
+        const double nt = (double)((n_v + 63) / 64);
         double best = 1.0;
-        for (int s = 2; s <= 4 && n_v >= (int64_t)s * 8 * 64; ++s) {
-            const double cost = (double)(((int64_t)rem * s + n_cu - 1) / n_cu) / s + 0.02 * rem / n_cu;
-            if (cost < best - 1e-9) { best = cost; t.split = s; }
+        for (int s = 2; s <= kMaxSplit && n_v >= (int64_t)s * 8 * 64 && rem * (s - 1) <= max_extra_slots(n_cu); ++s) {
+            const double rounds = (double)((rem * s + n_cu - 1) / n_cu);
+            const double cost = rounds * (1.0 / s + 4.0 / nt) + 0.02 * (double)rem / n_cu;
+            if (cost < best - 1e-12) { best = cost; t.split = s; }
         }
     }
     if (t.split > 1) {
@@ -106,13 +114,7 @@ inline int64_t tail_slots(const TailPlan& t, bool out_bf16) {
 }
 // Largest slot count any launch can need on a device with n_cu compute units.
 inline int64_t max_tail_slots(int n_cu, bool out_bf16) {
-    int64_t m = 0;
-    for (int rem = 1; rem < n_cu; ++rem) {
-        TailPlan t = plan_tail(256, rem, (int64_t)1 << 20, n_cu);
-        const int64_t s = tail_slots(t, out_bf16);
-        if (s > m) m = s;
-    }
-    return m;
+    return max_extra_slots(n_cu) + (out_bf16 ? n_cu - 1 : 0);
 }
 
 // Enqueue the forward kernel for B*Hg = BH (batch, head) pairs.  variant selects a tiling (0 = the

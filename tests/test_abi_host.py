@@ -238,9 +238,14 @@ def test_tail_plan_matches_the_rule_restated_in_python(pda):
     # the workloads: one 3-head group at 720p is 1 398 tiles = 5 rounds + 118 tiles, cut in 2
     assert pda.attn_tail_plan(1, 3, 119056, 119056, 128, 256) == {
         "n_tiles": 1398, "n_cut": 118, "split": 2, "part_keys": 59584, "workspace_slots": 118}
-    # 24 heads x 9 600: 912 tiles = 3 rounds + 144, cut in 3 (two rounds of thirds)
+    # 24 heads x 9 600: 912 tiles = 3 rounds + 144, cut in 5 (three rounds of fifths)
     assert pda.attn_tail_plan(1, 24, 9600, 9600, 128, 256) == {
-        "n_tiles": 912, "n_cut": 144, "split": 3, "part_keys": 3200, "workspace_slots": 288}
+        "n_tiles": 912, "n_cut": 144, "split": 5, "part_keys": 1920, "workspace_slots": 576}
+    # one head group of the 544 x 960 clip: 792 tiles = 3 rounds + 24, cut in 10 (240 items, one short round)
+    assert pda.attn_tail_plan(1, 3, 67576, 67476, 128, 256) == {
+        "n_tiles": 792, "n_cut": 24, "split": 10, "part_keys": 6784, "workspace_slots": 216}
+    # no plan needs more than 9/4 slots per compute unit for the parts beyond the first
+    assert max(pda.attn_tail_plan(1, 1, 256 * t, 1 << 20, 128, 256)["workspace_slots"] for t in range(1, 1025)) <= 576
     # d = 64 and an empty key set are never cut
     assert pda.attn_tail_plan(1, 2, 1024, 1024, 64, 256)["split"] == 1
     assert pda.attn_tail_plan(1, 3, 5000, 0, 128, 256)["n_cut"] == 0
