@@ -68,9 +68,11 @@ struct AttnParams {
 // are cut into `split` key ranges (2..16, each at least 8 key tiles long) so that the tail is made
 // of shorter items, run in ceil(rem * split / n_cu) rounds.  Cost of the tail in units of one
 // whole-tile sweep of nt key tiles:
-//     rounds * (1 / split + 4 / nt)  +  0.02 * rem / n_cu
-// (every item pays about four key-tile times for its prologue and its partial store; the last
-// term stands for the merge pass), against 1 for an uncut last round; the smallest cost wins,
+//     rounds * (1 / split + 28 / nt)  +  0.02 * rem / n_cu
+// (measured: every round of part items costs about 28 key-tile times on top of its share of the
+// sweep - prologue, partial store, less sharing of K/V between neighbouring workgroups - so short
+// sweeps such as 24 heads x 9 600 keys are left uncut; the last term stands for the merge pass),
+// against 1 for an uncut last round; the smallest cost wins,
 // the smaller split on ties.  The parts beyond the first of all cut tiles must fit the workspace:
 // rem * (split - 1) <= 9 * n_cu / 4.  (Cutting tiles of earlier, full rounds never pays.)
 // A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
@@ -95,7 +97,7 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
         double best = 1.0;
         for (int s = 2; s <= kMaxSplit && n_v >= (int64_t)s * 8 * 64 && rem * (s - 1) <= max_extra_slots(n_cu); ++s) {
             const double rounds = (double)((rem * s + n_cu - 1) / n_cu);
-            const double cost = rounds * (1.0 / s + 4.0 / nt) + 0.02 * (double)rem / n_cu;
+            const double cost = rounds * (1.0 / s + 28.0 / nt) + 0.02 * (double)rem / n_cu;
             if (cost < best - 1e-12) { best = cost; t.split = s; }
         }
     }

@@ -238,9 +238,9 @@ def test_tail_plan_matches_the_rule_restated_in_python(pda):
     # the workloads: one 3-head group at 720p is 1 398 tiles = 5 rounds + 118 tiles, cut in 2
     assert pda.attn_tail_plan(1, 3, 119056, 119056, 128, 256) == {
         "n_tiles": 1398, "n_cut": 118, "split": 2, "part_keys": 59584, "workspace_slots": 118}
-    # 24 heads x 9 600: 912 tiles = 3 rounds + 144, cut in 5 (three rounds of fifths)
+    # 24 heads x 9 600: 912 tiles = 3 rounds + 144; with sweeps of only 150 key tiles cutting does not pay
     assert pda.attn_tail_plan(1, 24, 9600, 9600, 128, 256) == {
-        "n_tiles": 912, "n_cut": 144, "split": 5, "part_keys": 1920, "workspace_slots": 576}
+        "n_tiles": 912, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
     # one head group of the 544 x 960 clip: 792 tiles = 3 rounds + 24, cut in 10 (240 items, one short round)
     assert pda.attn_tail_plan(1, 3, 67576, 67476, 128, 256) == {
         "n_tiles": 792, "n_cut": 24, "split": 10, "part_keys": 6784, "workspace_slots": 216}

@@ -268,7 +268,24 @@ def _assert_close_bf16(o16, l, ro, rl, what):
     assert (np.abs(l.astype(np.float64) - rl) / np.maximum(np.abs(rl), 1.0)).max() <= 1e-3, what
 
 
+def test_many_key_ranges_per_cut_tile():
+    """A launch of few tiles over a long key axis cuts every tile into the largest number of key
+    ranges (16); fp32 result against the oracle, masked tail inside the last range."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention
+    B, H, Sq, Skv, n_v = 1, 3, 600, 9000, 8975
+    plan = pda.attn_tail_plan(B, H, Sq, n_v, 128)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert plan["split"] == 16 and plan["n_cut"] == 9, plan
+    qb, kb, vb = gen_qkv(4711, B, H, Sq, Skv, 128, unit_rms=True)
+    o, l = _run(qb, kb, vb, 128 ** -0.5, n_v)
+    ro, rl = _oracle(qb, kb, vb, 128 ** -0.5, n_v)
+    assert_close(o, l, ro, rl, "16 key ranges")
+
+
 @pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut", [(1, 24, 700, 3000, 3000, True),    # 72 tiles, every one cut in three
+                                                     (1, 3, 600, 9000, 8975, True),     # 9 tiles, every one cut in sixteen
                                                      (1, 4, 16384, 600, 570, False),   # 256 tiles: one full round, none cut
                                                      (2, 5, 300, 2500, 2500, None)])
 def test_bf16_output_against_the_oracle(B, H, Sq, Skv, n_v, all_cut):

@@ -24,8 +24,8 @@ def test_noalloc_entry_matches_the_allocating_one_on_two_calls_in_a_row():
     from tests.util import assert_close
     scale = 128 ** -0.5
     # first call: 24 heads x 700 rows = 72 tiles, every one cut in three (144 scratch slots);
-    # second call, smaller: 5 heads x 300 rows = 10 tiles, each cut in four (30 slots, over the first call's leftovers)
-    cases = [(11, 1, 24, 700, 3000, 2990), (12, 1, 5, 300, 2100, 2100)]
+    # second call, smaller: 5 heads x 300 rows = 10 tiles, each cut in eleven (100 slots, over the first call's leftovers)
+    cases = [(11, 1, 24, 700, 3000, 2990), (12, 1, 5, 300, 6000, 6000)]
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     data = []
     for seed, B, H, Sq, Skv, n_v in cases:

@@ -53,7 +53,7 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     of pda_attn_tail_plan written out independently.  Tiles of 256 rows run one per compute unit
     at a time; the rem = n_tiles mod n_cu tiles of the last round are cut into s in 2..16 key
     ranges, each at least 8 key tiles of 64 long and with rem*(s-1) <= 9*n_cu/4 workspace slots,
-    when that lowers  ceil(rem*s/n_cu) * (1/s + 4/nt) + 0.02*rem/n_cu  (nt = key tiles of a whole
+    when that lowers  ceil(rem*s/n_cu) * (1/s + 28/nt) + 0.02*rem/n_cu  (nt = key tiles of a whole
     sweep) below 1: smallest cost, smallest s on ties."""
     plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
     if d != 128 or n_v <= 0 or BH * Sq <= 0:
@@ -69,7 +69,7 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
         if n_v < s * 512 or rem * (s - 1) > n_cu * 9 // 4:
             break
         rounds = float(-(-rem * s // n_cu))
-        cost = rounds * (1.0 / s + 4.0 / nt) + 0.02 * float(rem) / n_cu
+        cost = rounds * (1.0 / s + 28.0 / nt) + 0.02 * float(rem) / n_cu
         if cost < best - 1e-12:
             best, split = cost, s
     if split > 1:
