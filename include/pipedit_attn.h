@@ -3,9 +3,10 @@
  *
  * C ABI.  Every pointer is a DEVICE pointer unless the comment says "host".
  * The caller owns every tensor.  The library itself keeps one device workspace
- * per (device, stream) for the key-range partials of the d = 128 attention
- * kernel (see pda_attn_tail_plan).  It is allocated once, the first time a
- * launch on that stream needs one, with the largest size any launch can need
+ * per (device, stream) for the d = 128 attention kernel: its work counters and
+ * the key-range partials of cut query tiles (see pda_attn_tail_plan).  It is
+ * allocated once, the first time that kernel is launched on the stream, with
+ * the largest size any launch can need
  * on that device (831 slots of 132 096 bytes = 110 MB with 256 compute units);
  * it never grows and is kept until the process ends, so after that first call
  * per stream the attention entry points neither allocate nor free nor
@@ -113,11 +114,12 @@ int pda_attn_fwd_strided(const void* q, const void* k, const void* v, float* out
  * PDA_ERR_UNSUPPORTED and launches nothing (with 256 compute units no fp32-output launch needs
  * more than 576 slots, so nothing is rejected there).  All calls on one GPU share the one buffer,
  * whatever their stream: calls whose execution may overlap on a GPU race on it and must be
- * ordered by the caller (one stream, or events).  Nothing in it needs to start at zero: every
- * slot a launch reads was written by the same launch first.
+ * ordered by the caller (one stream, or events).  The buffer also holds the kernel's two work
+ * counters, which are zero when the library is loaded and which every launch leaves at zero;
+ * every partial slot a launch reads was written by the same launch first.
  */
 #define PDA_NOALLOC_MAX_SLOTS 576
-#define PDA_NOALLOC_SCRATCH_BYTES 76087296 /* 576 * (256*128 + 256) * 4 */
+#define PDA_NOALLOC_SCRATCH_BYTES 76087552 /* 576 * (256*128 + 256) * 4 for the partials + 256 for the work counters */
 int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out, float* lse,
                          int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
                          int64_t kv_valid_len, int64_t q_offset, void* stream);

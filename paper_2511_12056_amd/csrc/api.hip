@@ -107,12 +107,12 @@ hipError_t device_cu_count(int* n_cu) {
 
 namespace {
 
-// ---- workspaces for the key-range partials of the software-pipelined kernel -------------------
+// ---- workspaces of the software-pipelined kernel: key-range partials and the work counters ------
 //
-// (1) Cached: one buffer per (device, stream), allocated the first time a launch on that stream
-// needs a workspace, with the largest size any launch can need on the device (a function of its CU
-// count alone: fewer than n_cu cut tiles, at most 4 ranges each), so it never grows, is never
-// freed and the launch path never synchronises.  Launches on one stream are ordered and share it.
+// (1) Cached: one buffer per (device, stream), allocated (and its counters zeroed) the first time
+// the kernel is launched on that stream, with the largest size any launch can need on the device
+// (a function of its CU count alone), so it never grows, is never freed and the launch path never
+// synchronises after that.  Launches on one stream are ordered and share it.
 struct CachedWs { float* ptr; int64_t slots; };
 int cached_workspace(hipStream_t st, int64_t need_slots, CachedWs* out) {
     static std::mutex mu;
@@ -126,13 +126,16 @@ int cached_workspace(hipStream_t st, int64_t need_slots, CachedWs* out) {
     if (!w.ptr) {
         const int64_t slots = pda::max_tail_slots(n_cu, true);
         void* ptr = nullptr;
-        e = hipMalloc(&ptr, (size_t)slots * pda::kSlotFloats * sizeof(float));
+        const size_t bytes = ((size_t)slots * pda::kSlotFloats + pda::kCounterFloats) * sizeof(float);
+        e = hipMalloc(&ptr, bytes);
         if (e == hipErrorOutOfMemory) {
             (void)hipGetLastError();
-            return fail(PDA_ERR_NOMEM, "no device memory for the %lld MB workspace of this stream",
-                        (long long)((size_t)slots * pda::kSlotFloats * sizeof(float) >> 20));
+            return fail(PDA_ERR_NOMEM, "no device memory for the %lld MB workspace of this stream", (long long)(bytes >> 20));
         }
         if (e != hipSuccess) return hip_fail(e, "workspace allocation");
+        // the work counters start at zero (every launch leaves them at zero again); part of this one-time set-up
+        e = hipMemset(static_cast<float*>(ptr) + (size_t)slots * pda::kSlotFloats, 0, pda::kCounterFloats * sizeof(float));
+        if (e != hipSuccess) { (void)hipFree(ptr); return hip_fail(e, "workspace set-up"); }
         w.ptr = static_cast<float*>(ptr);
         w.slots = slots;
     }
@@ -146,8 +149,8 @@ int cached_workspace(hipStream_t st, int64_t need_slots, CachedWs* out) {
 // In host code the array's NAME is not a device address: only the pointer hipGetSymbolAddress
 // returns is ever handed to a kernel.
 constexpr int64_t kStaticSlots = PDA_NOALLOC_MAX_SLOTS;
-static __device__ __align__(256) float scratch[kStaticSlots * pda::kSlotFloats];
-static_assert(sizeof(float) * kStaticSlots * pda::kSlotFloats == PDA_NOALLOC_SCRATCH_BYTES, "header and library disagree");
+static __device__ __align__(256) float scratch[kStaticSlots * pda::kSlotFloats + pda::kCounterFloats];   // zero-initialised
+static_assert(sizeof(scratch) == PDA_NOALLOC_SCRATCH_BYTES, "header and library disagree");
 
 int static_workspace(float** out) {
     static std::mutex mu;
@@ -181,23 +184,22 @@ int launch_checked(const void* q, const void* k, const void* v, float* out, floa
         int n_cu = 0;
         hipError_t e = pda::device_cu_count(&n_cu);
         if (e != hipSuccess) return hip_fail(e, "device query");
+        // every launch of this kernel uses a workspace: its work counters, and the partial slots of cut tiles
         const int64_t need = pda::tail_slots(pda::plan_tail(Sq, B * hg, n_v, n_cu), out_bf16);
-        if (need > 0) {
-            if (kind == WS_STATIC) {
-                if (need > kStaticSlots)
-                    return fail(PDA_ERR_UNSUPPORTED, "this launch needs %lld partial slots (%lld bytes) of scratch; the static buffer holds %lld (%lld bytes)",
-                                (long long)need, (long long)(need * pda::kSlotFloats * sizeof(float)),
-                                (long long)kStaticSlots, (long long)PDA_NOALLOC_SCRATCH_BYTES);
-                int rc = static_workspace(&ws);
-                if (rc != PDA_OK) return rc;
-                ws_slots = kStaticSlots;
-            } else {
-                CachedWs w{};
-                int rc = cached_workspace(st, need, &w);
-                if (rc != PDA_OK) return rc;
-                ws = w.ptr;
-                ws_slots = w.slots;
-            }
+        if (kind == WS_STATIC) {
+            if (need > kStaticSlots)
+                return fail(PDA_ERR_UNSUPPORTED, "this launch needs %lld partial slots (%lld bytes) of scratch; the static buffer holds %lld (%lld bytes)",
+                            (long long)need, (long long)(need * pda::kSlotFloats * sizeof(float)),
+                            (long long)kStaticSlots, (long long)PDA_NOALLOC_SCRATCH_BYTES);
+            int rc = static_workspace(&ws);
+            if (rc != PDA_OK) return rc;
+            ws_slots = kStaticSlots;
+        } else {
+            CachedWs w{};
+            int rc = cached_workspace(st, need, &w);
+            if (rc != PDA_OK) return rc;
+            ws = w.ptr;
+            ws_slots = w.slots;
         }
     }
     hipError_t e = launch_strided(q, k, v, out, lse, B, hg, Sq, d, s, scale, n_v, st, variant, base2, out_bf16, ws, ws_slots);

@@ -95,18 +95,31 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     constexpr int RPC = 1024 / (D * 2);   // 4 rows per chunk
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int next_item;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lh = lane >> 5;
 
-    // ---- work item -> (query tile, head, key range)
-    int tile = blockIdx.x, part = 0;
-    if (tile >= p.n_full && p.split > 1) {
-        const int idx = tile - p.n_full;
-        tile = p.n_full + idx / p.split;
-        part = idx - (idx / p.split) * p.split;
+    // Persistent workgroups (one per CU) take work items in index order from a device counter: the
+    // chip's XCDs run at persistently different speeds (several percent apart under the power
+    // limit) and the hardware deals the workgroups of a grid to them round robin, so a grid with
+    // one workgroup per item would end with the slowest XCD while the others idle.
+    for (;;) {
+    if (tid == 0) next_item = atomicAdd(p.counter, 1);
+    __syncthreads();
+    const int item = __builtin_amdgcn_readfirstlane(next_item);
+    __syncthreads();                                   // everyone has read it before the next fetch overwrites it
+    if (item >= p.n_items) break;
+
+    // ---- work item -> (query tile, head, key range).  Items [0, n_full) are whole tiles; then the
+    // cut tiles' key ranges, range-major, so that the items in flight at any time sweep the same keys.
+    int tile = item, part = 0;
+    if (item >= p.n_full) {
+        const int idx = item - p.n_full;
+        part = idx / p.n_cut;
+        tile = p.n_full + (idx - part * p.n_cut);
     }
     const int bh = tile / p.tiles_per_head;
     const int q_tile = tile - bh * p.tiles_per_head;
@@ -574,6 +587,18 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             if (lh == 0) lp[row - row_sub] = mc_run[nq] * 0.6931471805599453f + __logf(l_tot);
         }
     }
+    }   // next work item
+
+    // The last workgroup to leave puts both counters back to zero for the next launch that uses this
+    // workspace (launches sharing a workspace are ordered on one stream).  Every workgroup has made
+    // its last fetch before it counts itself out, so nobody fetches after the reset.
+    if (tid == 0) {
+        __threadfence();
+        if (atomicAdd(p.counter + 1, 1) == (int)gridDim.x - 1) {
+            __hip_atomic_store(p.counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.counter + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 // Folds the key-range partials of the cut tiles into out/lse (in place): per row,
@@ -593,30 +618,27 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     // fp32 out: part 0 sits in out/lse and parts 1.. in the workspace; bf16 out: all parts in the workspace
     const int n_ws = p.out_bf16 ? p.split : p.split - 1;
     const int64_t slot0 = (int64_t)(tile - p.n_full) * n_ws;
-    float l[kMaxSplit];
-    float4 x[kMaxSplit];
-    float m = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < kMaxSplit; ++j) {
-        if (j >= p.split) break;
+    // one pass with a running reference (the parts of a cut tile are never empty: lse is finite)
+    float m = -INFINITY, tot = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < p.split; ++j) {
+        float lj;
+        float4 xj;
         if (j == 0 && !p.out_bf16) {
-            l[0] = *lp;
-            x[0] = reinterpret_cast<const float4*>(p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D)[c4];
+            lj = *lp;
+            xj = reinterpret_cast<const float4*>(p.out + (int64_t)b * p.o_bs + (int64_t)h * p.o_hs + row * D)[c4];
         } else {
             const int64_t slot = slot0 + (p.out_bf16 ? j : j - 1);
-            l[j] = p.part_lse[slot * M + r_in];
-            x[j] = reinterpret_cast<const float4*>(p.part_out + (slot * M + r_in) * D)[c4];
+            lj = p.part_lse[slot * M + r_in];
+            xj = reinterpret_cast<const float4*>(p.part_out + (slot * M + r_in) * D)[c4];
         }
-        m = fmaxf(m, l[j]);
-    }
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float tot = 0.f;
-#pragma unroll
-    for (int j = 0; j < kMaxSplit; ++j) {
-        if (j >= p.split) break;
-        const float w = __expf(l[j] - m);
-        acc.x += w * x[j].x; acc.y += w * x[j].y; acc.z += w * x[j].z; acc.w += w * x[j].w;
-        tot += w;
+        const float m_new = fmaxf(m, lj);
+        const float a_old = __expf(m - m_new);          // 0 on the first part
+        const float w = __expf(lj - m_new);
+        acc.x = acc.x * a_old + w * xj.x; acc.y = acc.y * a_old + w * xj.y;
+        acc.z = acc.z * a_old + w * xj.z; acc.w = acc.w * a_old + w * xj.w;
+        tot = tot * a_old + w;
+        m = m_new;
     }
     const float inv = 1.0f / tot;
     acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
@@ -642,15 +664,19 @@ static hipError_t launch_sp(AttnParams p, int BH, float* ws, int64_t ws_slots, h
     }
     const TailPlan t = plan_tail(p.Sq, BH, p.n_v, n_cu);
     const int64_t slots = tail_slots(t, p.out_bf16 != 0);
-    if (slots > 0 && (ws == nullptr || slots > ws_slots)) return hipErrorInvalidValue;
+    if (ws == nullptr || slots > ws_slots) return hipErrorInvalidValue;
     p.tiles_per_head = t.tiles_per_head;
     p.split = t.split;
+    p.n_cut = (int)t.n_cut;
     p.n_full = (int)(t.n_tiles - t.n_cut);
     p.part_keys = t.part_keys;
     p.part_out = slots ? ws : nullptr;
     p.part_lse = slots ? ws + slots * (M * D) : nullptr;
+    p.counter = reinterpret_cast<int*>(ws + ws_slots * kSlotFloats);     // two ints behind the slots, zero between launches
     const int64_t items = p.n_full + t.n_cut * t.split;
-    hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(512 / NQ), smem, st, p);
+    p.n_items = (int)items;
+    const unsigned grid = (unsigned)(items < n_cu ? items : n_cu);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512 / NQ), smem, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || t.split <= 1) return e;
     hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(t.n_cut * (M / 8))), dim3(256), 0, st, p, (int)t.n_cut);

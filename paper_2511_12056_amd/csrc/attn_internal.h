@@ -47,34 +47,38 @@ struct AttnParams {
     int Hg;                 // heads in this launch
     float scale;            // softmax scale
     float scale_log2e;      // scale * log2(e)
-    // Work items of the software-pipelined kernel (1-D grid).  Items [0, n_full) are whole 256-row
-    // query tiles (tile = item; head = tile / tiles_per_head).  Every later tile is cut into `split`
-    // key ranges of part_keys keys, one item each, so that the last, partly filled round of
-    // workgroups finishes sooner; part 0 writes out/lse, parts >= 1 write normalised partials to
-    // part_out/part_lse, which a merge pass folds into out/lse.  split <= 1: no cut.
+    // Work items of the software-pipelined kernel, taken in index order by persistent workgroups.
+    // Items [0, n_full) are whole 256-row query tiles (tile = item; head = tile / tiles_per_head).
+    // Every later tile is cut into `split` key ranges of part_keys keys, one item each (item =
+    // n_full + part * n_cut + cut tile), so that the end of the launch is made of short items;
+    // part 0 writes out/lse, parts >= 1 write normalised partials to part_out/part_lse, which a
+    // merge pass folds into out/lse.  split <= 1: no cut.
     int tiles_per_head;
     int n_full;
     int split;
     int64_t part_keys;
     float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
     float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
+    int n_cut;              // number of cut tiles (the last n_cut of the launch)
+    int n_items;            // n_full + n_cut * split
+    int* counter;           // two ints, zero between launches: next work item, workgroups that have finished
     int out_bf16;           // software-pipelined kernel: `out` points to bf16 elements (same element strides)
     int base2;              // scores are already in log2 units: weights 2^(q.k), scale_log2e == 1
     int redo_always;        // software-pipelined kernel: sweep every item a second time with the running max (testing aid)
 };
 
-// Tail plan of the software-pipelined kernel (d = 128, 256-row query tiles, one workgroup per CU
-// at a time, so tiles run in rounds of n_cu).  The `rem` tiles of the last, partly filled round
-// are cut into `split` key ranges (2..16, each at least 8 key tiles long) so that the tail is made
-// of shorter items, run in ceil(rem * split / n_cu) rounds.  Cost of the tail in units of one
-// whole-tile sweep of nt key tiles:
-//     rounds * (1 / split + 28 / nt)  +  0.02 * rem / n_cu
-// (measured: every round of part items costs about 28 key-tile times on top of its share of the
-// sweep - prologue, partial store, less sharing of K/V between neighbouring workgroups - so short
-// sweeps such as 24 heads x 9 600 keys are left uncut; the last term stands for the merge pass),
-// against 1 for an uncut last round; the smallest cost wins,
-// the smaller split on ties.  The parts beyond the first of all cut tiles must fit the workspace:
-// rem * (split - 1) <= 9 * n_cu / 4.  (Cutting tiles of earlier, full rounds never pays.)
+// Tail plan of the software-pipelined kernel (d = 128, 256-row query tiles, one persistent
+// workgroup per CU taking items in order).  Whole tiles are long items (a 119 056-key sweep takes
+// 3 ms), the XCDs run at different speeds, and a launch ends when the last item does; so the
+// `rem` = n_tiles mod n_cu tiles that do not fill a round of whole tiles are cut into `split` key
+// ranges, short items that the workgroups pick up as they run out of whole tiles.  Measured on
+// the device: about three part items per CU balance the end of a launch; parts shorter than about
+// 100 key tiles cost more (prologue, partial store, merge) than they recover, so short sweeps are
+// left uncut.  Rule:
+//     split = round(3 * n_cu / rem), at least 2, at most the smallest of
+//             16, nt / 100 (nt = key tiles of a whole sweep), n_v / 512,
+//             1 + (9 * n_cu / 4) / rem   (workspace: the parts beyond the first must fit),
+//     lowered until the last range is not empty; uncut if that leaves less than 2 or rem = 0.
 // A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
 // the last n_cut of the launch's n_tiles tiles in (batch, head, query tile) order.
 constexpr int kMaxSplit = 16;
@@ -86,6 +90,7 @@ struct TailPlan {
     int64_t part_keys;      // keys per range (multiple of 64); 0 if no tile is cut
 };
 inline int64_t max_extra_slots(int n_cu) { return (int64_t)n_cu * 9 / 4; }
+inline int64_t part_keys_for(int64_t n_v, int s) { return ((n_v + s - 1) / s + 63) / 64 * 64; }
 inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
     TailPlan t{};
     t.tiles_per_head = (int)((Sq + 255) / 256);
@@ -93,22 +98,28 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
     t.split = 1;
     const int64_t rem = t.n_tiles % n_cu;
     if (rem) {
-        const double nt = (double)((n_v + 63) / 64);
-        double best = 1.0;
-        for (int s = 2; s <= kMaxSplit && n_v >= (int64_t)s * 8 * 64 && rem * (s - 1) <= max_extra_slots(n_cu); ++s) {
-            const double rounds = (double)((rem * s + n_cu - 1) / n_cu);
-            const double cost = rounds * (1.0 / s + 28.0 / nt) + 0.02 * (double)rem / n_cu;
-            if (cost < best - 1e-12) { best = cost; t.split = s; }
-        }
+        const int64_t nt = (n_v + 63) / 64;
+        int64_t s_max = kMaxSplit;
+        if (nt / 100 < s_max) s_max = nt / 100;
+        if (n_v / 512 < s_max) s_max = n_v / 512;
+        if (1 + max_extra_slots(n_cu) / rem < s_max) s_max = 1 + max_extra_slots(n_cu) / rem;
+        int64_t s = (6 * (int64_t)n_cu + rem) / (2 * rem);                 // round(3 * n_cu / rem)
+        if (s < 2) s = 2;
+        if (s > s_max) s = s_max;
+        while (s >= 2 && (s - 1) * part_keys_for(n_v, (int)s) >= n_v) --s;   // the last range must not be empty
+        if (s >= 2) t.split = (int)s;
     }
     if (t.split > 1) {
         t.n_cut = rem;
-        t.part_keys = ((n_v + t.split - 1) / t.split + 63) / 64 * 64;
+        t.part_keys = part_keys_for(n_v, t.split);
     }
     return t;
 }
 // One workspace slot holds one key-range partial of a cut tile: 256 x 128 values + 256 lse.
+// A workspace of n slots is n * kSlotFloats floats followed by kCounterFloats floats that hold the
+// kernel's two work counters (zero whenever no launch is running on it).
 constexpr size_t kSlotFloats = 256 * 128 + 256;
+constexpr size_t kCounterFloats = 64;
 // Slots a launch needs: parts 1.. of every cut tile (part 0 goes to out/lse), or all parts when
 // out is bf16 (the merge pass then needs part 0 in fp32 as well).
 inline int64_t tail_slots(const TailPlan& t, bool out_bf16) {

@@ -235,17 +235,21 @@ def test_tail_plan_matches_the_rule_restated_in_python(pda):
         got = pda.attn_tail_plan(1, BH, Sq, n_v, d, n_cu)
         want = tail_plan(BH, Sq, n_v, d, n_cu)
         assert got == want, (n_cu, BH, Sq, n_v, d, got, want)
-    # the workloads: one 3-head group at 720p is 1 398 tiles = 5 rounds + 118 tiles, cut in 2
+    # the workloads: one 3-head group at 720p is 1 398 tiles = 5 x 256 + 118; round(768/118) = 7 ranges, 5 fit the workspace
     assert pda.attn_tail_plan(1, 3, 119056, 119056, 128, 256) == {
-        "n_tiles": 1398, "n_cut": 118, "split": 2, "part_keys": 59584, "workspace_slots": 118}
-    # 24 heads x 9 600: 912 tiles = 3 rounds + 144; with sweeps of only 150 key tiles cutting does not pay
+        "n_tiles": 1398, "n_cut": 118, "split": 5, "part_keys": 23872, "workspace_slots": 472}
+    # 24 heads x 9 600: 912 tiles = 3 x 256 + 144; sweeps of only 150 key tiles are left uncut
     assert pda.attn_tail_plan(1, 24, 9600, 9600, 128, 256) == {
         "n_tiles": 912, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
-    # one head group of the 544 x 960 clip: 792 tiles = 3 rounds + 24, cut in 10 (240 items, one short round)
+    # one head group of the 544 x 960 clip: 792 tiles = 3 x 256 + 24, 1 055 key tiles: at most 10 ranges
     assert pda.attn_tail_plan(1, 3, 67576, 67476, 128, 256) == {
         "n_tiles": 792, "n_cut": 24, "split": 10, "part_keys": 6784, "workspace_slots": 216}
-    # no plan needs more than 9/4 slots per compute unit for the parts beyond the first
-    assert max(pda.attn_tail_plan(1, 1, 256 * t, 1 << 20, 128, 256)["workspace_slots"] for t in range(1, 1025)) <= 576
+    # no plan needs more than 9/4 slots per compute unit for the parts beyond the first, and no range is empty
+    for t in range(1, 1025):
+        for n_v in (1 << 20, 12800, 8200, 8193, 51200 + t):
+            pl = pda.attn_tail_plan(1, 1, 256 * t, n_v, 128, 256)
+            assert pl["workspace_slots"] <= 576
+            assert pl["split"] == 1 or (pl["split"] - 1) * pl["part_keys"] < n_v
     # d = 64 and an empty key set are never cut
     assert pda.attn_tail_plan(1, 2, 1024, 1024, 64, 256)["split"] == 1
     assert pda.attn_tail_plan(1, 3, 5000, 0, 128, 256)["n_cut"] == 0

@@ -50,11 +50,11 @@ def assert_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
 
 def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     """Which query tiles a d = 128 attention launch computes as merged key-range partials: the rule
-    of pda_attn_tail_plan written out independently.  Tiles of 256 rows run one per compute unit
-    at a time; the rem = n_tiles mod n_cu tiles of the last round are cut into s in 2..16 key
-    ranges, each at least 8 key tiles of 64 long and with rem*(s-1) <= 9*n_cu/4 workspace slots,
-    when that lowers  ceil(rem*s/n_cu) * (1/s + 28/nt) + 0.02*rem/n_cu  (nt = key tiles of a whole
-    sweep) below 1: smallest cost, smallest s on ties."""
+    of pda_attn_tail_plan written out independently.  Tiles of 256 rows; the rem = n_tiles mod n_cu
+    tiles that do not fill a round of whole tiles are cut into s = round(3*n_cu/rem) key ranges,
+    at least 2 and at most min(16, nt // 100, n_v // 512, 1 + (9*n_cu//4) // rem) with nt the key
+    tiles (of 64) of a whole sweep, lowered until the last range is not empty; uncut if that leaves
+    less than 2.  A range holds ceil(n_v / s) keys rounded up to a multiple of 64."""
     plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
     if d != 128 or n_v <= 0 or BH * Sq <= 0:
         return plan
@@ -63,18 +63,17 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     rem = tiles % n_cu
     if rem == 0:
         return plan
-    nt = float(-(-n_v // 64))
-    best, split = 1.0, 1
-    for s in range(2, 17):
-        if n_v < s * 512 or rem * (s - 1) > n_cu * 9 // 4:
-            break
-        rounds = float(-(-rem * s // n_cu))
-        cost = rounds * (1.0 / s + 28.0 / nt) + 0.02 * float(rem) / n_cu
-        if cost < best - 1e-12:
-            best, split = cost, s
-    if split > 1:
-        per = -(-n_v // split)
-        plan.update(n_cut=rem, split=split, part_keys=-(-per // 64) * 64, workspace_slots=rem * (split - 1))
+    nt = -(-n_v // 64)
+
+    def keys(s):
+        return -(-(-(-n_v // s)) // 64) * 64
+
+    s_max = min(16, nt // 100, n_v // 512, 1 + (9 * n_cu // 4) // rem)
+    s = min(max((6 * n_cu + rem) // (2 * rem), 2), s_max)
+    while s >= 2 and (s - 1) * keys(s) >= n_v:
+        s -= 1
+    if s >= 2:
+        plan.update(n_cut=rem, split=s, part_keys=keys(s), workspace_slots=rem * (s - 1))
     return plan
 
 
