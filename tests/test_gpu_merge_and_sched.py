@@ -271,3 +271,26 @@ def test_strided_views_equal_compact_copies():
     torch.cuda.synchronize()
     assert torch.equal(out[:, 1:3], ref[:, 1:3]) and torch.equal(lse[:, 1:3], rlse[:, 1:3])
     assert (out[:, 0] == 0).all() and (out[:, 3] == 0).all()
+
+
+def test_launches_on_two_streams_do_not_share_a_workspace():
+    """Two attention launches whose tiles are cut into key ranges, enqueued on two streams without
+    any ordering between them: each stream has its own partial slots and work counters, so both
+    give bit for bit what they give alone."""
+    import torch
+    import paper_2511_12056_amd as pda
+    shapes = [(1, 24, 700, 12900, 12850), (1, 5, 300, 19300, 19300)]
+    data = []
+    for i, (B, H, Sq, Skv, n_v) in enumerate(shapes):
+        qb, kb, vb = gen_qkv(60 + i, B, H, Sq, Skv, 128, unit_rms=True)
+        q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+        ref, rlse = _fwd(q, k, v, 0.09, n_v)
+        data.append((q, k, v, n_v, ref, rlse, torch.full_like(ref, float("nan")), torch.full_like(rlse, float("nan"))))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        for st, (q, k, v, n_v, _, _, out, lse) in zip(streams, data):
+            pda.attn_fwd(q, k, v, out, lse, 0.09, n_v, stream=st)
+    torch.cuda.synchronize()
+    for (_, _, _, _, ref, rlse, out, lse) in data:
+        assert torch.equal(out, ref) and torch.equal(lse, rlse)

@@ -75,3 +75,34 @@ def test_noalloc_entry_covers_uncut_launches_and_d64_and_rejects_bad_arguments()
     assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 9, 0, None) == 1
     assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 8, -1, None) == 1
     assert f(None, None, None, None, None, 1, 1, 0, 8, 128, 1.0, 8, 0, None) == 0
+
+
+def test_noalloc_entry_under_graph_capture():
+    """What the entry point is for: captured into a HIP graph (after one call outside the capture,
+    which looks up the static buffer) and replayed several times, with eager work and
+    synchronisations between the replays; every replay must reproduce the eager result."""
+    import torch
+    import paper_2511_12056_amd as pda
+    B, H, Sq, Skv, n_v = 1, 24, 700, 12900, 12850
+    scale = 128 ** -0.5
+    qb, kb, vb = gen_qkv(21, B, H, Sq, Skv, 128, unit_rms=True)
+    q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+    ref = torch.empty(B, H, Sq, 128, device="cuda"); rlse = torch.empty(B, H, Sq, device="cuda")
+    out = torch.empty_like(ref); lse = torch.empty_like(rlse)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        pda.attn_fwd_noalloc(q, k, v, ref, rlse, scale, n_v, stream=side)          # eager; also the set-up call
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pda.attn_fwd_noalloc(q, k, v, out, lse, scale, n_v, stream=side)
+    for rep in range(3):
+        out.fill_(float("nan")); lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref) and torch.equal(lse, rlse), rep
+        # eager work between the replays, through the same static buffer
+        pda.attn_fwd_noalloc(q, k, v, out, lse, scale, n_v)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
