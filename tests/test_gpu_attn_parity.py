@@ -330,3 +330,36 @@ def test_bf16_output_is_the_rounded_fp32_output(B, H, Sq, Skv, n_v):
     torch.cuda.synchronize()
     assert torch.equal(o16, o32.to(torch.bfloat16))
     assert torch.equal(l16, l32)
+
+
+def test_key_axis_beyond_2_gib():
+    """One head whose K (and V) tensor is larger than 2^31 bytes (8.4 M keys x 256 B): every key
+    address needs 64-bit arithmetic.  Four query rows; the launch's single tile is cut into 16 key
+    ranges.  Oracle: the pinned per-chunk oracle on chunks of 1 M keys, combined with the pinned
+    oracle merge (bounds host memory)."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention_head, merge_partials
+    Sq, Skv, d = 4, 8_400_000, 128
+    n_v = Skv - 37
+    rng = np.random.default_rng(2511)
+    qb = f32_to_bf16_bits(rng.standard_normal((1, 1, Sq, d), dtype=np.float32))
+    kb = np.empty((1, 1, Skv, d), dtype=np.uint16)
+    vb = np.empty((1, 1, Skv, d), dtype=np.uint16)
+    step = 1 << 20
+    for a in range(0, Skv, step):
+        b = min(Skv, a + step)
+        kb[0, 0, a:b] = f32_to_bf16_bits(rng.standard_normal((b - a, d), dtype=np.float32))
+        vb[0, 0, a:b] = f32_to_bf16_bits(rng.standard_normal((b - a, d), dtype=np.float32))
+    # make the last keys matter: the query rows point at keys near the end of the tensor
+    kb[0, 0, n_v - 3] = f32_to_bf16_bits(bf16_bits_to_f32(qb[0, 0, 1]) * np.float32(2.5))
+    kb[0, 0, n_v - 1] = f32_to_bf16_bits(bf16_bits_to_f32(qb[0, 0, 2]) * np.float32(2.0))
+    scale = d ** -0.5
+    o, l = _run(qb, kb, vb, scale, n_v)
+    parts = []
+    for a in range(0, n_v, step):
+        b = min(n_v, a + step)
+        parts.append(attention_head(qb[0, 0], kb[0, 0, a:b], vb[0, 0, a:b], scale))
+    ro, rl = merge_partials([p[0] for p in parts], [p[1] for p in parts])
+    assert rl[1] > rl[0] + 1 and rl[2] > rl[0] + 1            # the planted keys near the end carry weight
+    assert_close(o[0, 0], l[0, 0], ro, rl, "K larger than 2 GiB")
