@@ -269,3 +269,47 @@ def test_pack_with_folded_scale_feeds_base2_attention():
     for hh in range(H):
         ro, rl = attention_head(qo[0, hh], ko[0, hh], vo[0, hh], math.log(2.0), S)
         assert_close(out[0, hh].cpu().numpy(), lse[0, hh].cpu().numpy(), ro, rl, f"folded scale head {hh}")
+
+
+def test_streaming_kernels_beyond_2_to_31_elements():
+    """Post-processing, pack and merge on tensors of more than 2^31 elements (64-bit offsets, grids
+    that use all three dimensions), generated on the device; sampled rows against the oracles."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import merge_partials
+    from oracle.pack import pack_heads
+    from oracle.pipesp_layout import psi
+    rows, h, n, D = 700_001, 3, 8, 128                      # 2.15e9 floats
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    rng = np.random.default_rng(5)
+    pick = np.unique(np.concatenate([[0, 1, rows - 2, rows - 1, 65534, 65535, 65536, 524287, 524288],
+                                     rng.choice(rows, size=1500, replace=False)]))
+    idx = torch.from_numpy(pick).cuda()
+    x = torch.randn(rows, h * n, D, device="cuda", generator=g)
+    # Algorithm 1 steps 10-13 on one concatenated tensor
+    hidden = torch.empty_like(x)
+    pda.pipesp_postprocess(x, h, n, hidden)
+    torch.cuda.synchronize()
+    assert np.array_equal(hidden[idx].cpu().numpy(), psi(x[idx].cpu().numpy(), h, n))
+    del hidden
+    # pack: x as [1, S, H, d] token-major
+    y = torch.empty(1, h * n, rows, D, dtype=torch.bfloat16, device="cuda")
+    pda.pack_heads(x.view(1, rows, h * n, D), y, unit_rms=False)
+    torch.cuda.synchronize()
+    got = y[0][:, idx].float().cpu().numpy().astype(np.float64)                       # [H, picked, d]
+    want = pack_heads(x[idx].cpu().numpy()[None], unit_rms=False)[0]                # [H, picked, d]
+    assert np.array_equal(got, want)
+    del y
+    # merge of two partials of rows*24 rows x 128 values... the same buffer viewed as [rows*24, 128]
+    R = rows * h * n
+    lse = [torch.randn(R, device="cuda", generator=g) * 3 for _ in range(2)]
+    p1 = torch.randn(R, D, device="cuda", generator=g)
+    out = torch.empty(R, D, device="cuda")
+    lo = torch.empty(R, device="cuda")
+    pda.attn_merge([x.view(R, D), p1], lse, out, lo)
+    torch.cuda.synchronize()
+    rpick = np.unique(np.concatenate([[0, R - 1, (1 << 24) - 1, 1 << 24], rng.choice(R, size=2000, replace=False)]))
+    ridx = torch.from_numpy(rpick).cuda()
+    ro, rl = merge_partials([x.view(R, D)[ridx].cpu().numpy(), p1[ridx].cpu().numpy()], [l[ridx].cpu().numpy() for l in lse])
+    assert np.abs(out[ridx].cpu().numpy() - ro).max() < 2e-5
+    assert np.abs(lo[ridx].cpu().numpy() - rl).max() < 1e-5
