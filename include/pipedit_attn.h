@@ -128,9 +128,10 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
  * How a d = 128 attention launch over B*H (batch, head) pairs is cut into work items (host only;
  * every pointer below is a HOST pointer; no device work).  The kernel takes 256-row query tiles,
  * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles
- * (in (batch, head, query tile) order: the partly filled last round) are each computed as `split`
- * (2..16) partial attentions over key ranges of part_keys keys and merged with the formula of
- * pda_attn_merge; all other tiles are swept in one pass.  Hence two launches agree bit for bit
+ * (in (batch, head, query tile) order: the partly filled last round; all tiles of a launch
+ * with fewer tiles than compute units) are each computed as `split` (2..16) partial attentions
+ * over key ranges of part_keys keys and merged with the formula of pda_attn_merge; all other
+ * tiles are swept in one pass.  Hence two launches agree bit for bit
  * on every row that lies in an uncut tile of both, and to the rounding of the probabilities on
  * the others.  n_cu: compute units of the device (0 = ask the current device).  Outputs (any may
  * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_keys, and

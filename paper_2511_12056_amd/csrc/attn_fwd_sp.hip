@@ -665,6 +665,7 @@ static hipError_t launch_sp(AttnParams p, int BH, float* ws, int64_t ws_slots, h
     const TailPlan t = plan_tail(p.Sq, BH, p.n_v, n_cu);
     const int64_t slots = tail_slots(t, p.out_bf16 != 0);
     if (ws == nullptr || slots > ws_slots) return hipErrorInvalidValue;
+    if (t.split > 1 && (int64_t)(t.split - 1) * t.part_keys >= p.n_v) return hipErrorInvalidValue;   // no key range may be empty
     p.tiles_per_head = t.tiles_per_head;
     p.split = t.split;
     p.n_cut = (int)t.n_cut;

@@ -209,7 +209,7 @@ def test_reference_tilings_and_forced_second_sweep_agree_with_the_oracle():
     import paper_2511_12056_amd as pda
     from oracle import attention
     shapes = [(1, 2, 515, 1100, 1050, 0.09), (2, 1, 300, 4200, 4200, 0.3), (1, 3, 777, 64, 40, 0.0883883),
-              (1, 24, 700, 12900, 12850, 0.0883883)]                # the last one: every tile cut in two
+              (1, 24, 700, 12900, 12850, 0.0883883)]                # the last one: every tile cut in three
     for i, (B, H, Sq, Skv, n_v, scale) in enumerate(shapes):
         qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, 128, unit_rms=bool(i % 2))
         ro, rl = attention(qb, kb, vb, scale, n_v)
@@ -286,7 +286,7 @@ def test_many_key_ranges_per_cut_tile():
     assert_close(o, l, ro, rl, "16 key ranges")
 
 
-@pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut", [(1, 24, 700, 12900, 12850, True),  # 72 tiles, every one cut in two
+@pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut", [(1, 24, 700, 12900, 12850, True),  # 72 tiles, every one cut in three
                                                      (1, 3, 600, 102500, 102440, True), # 9 tiles, every one cut in sixteen
                                                      (1, 4, 16384, 600, 570, False),   # 256 tiles: one full round, none cut
                                                      (2, 5, 300, 2500, 2500, None)])

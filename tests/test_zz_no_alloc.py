@@ -23,8 +23,8 @@ def test_noalloc_entry_matches_the_allocating_one_on_two_calls_in_a_row():
     from oracle import attention
     from tests.util import assert_close
     scale = 128 ** -0.5
-    # first call: 24 heads x 700 rows = 72 tiles, every one cut in two (72 scratch slots);
-    # second call, smaller: 5 heads x 300 rows = 10 tiles, each cut in three (20 slots, over the first call's leftovers)
+    # first call: 24 heads x 700 rows = 72 tiles, every one cut in three (144 scratch slots);
+    # second call, smaller: 5 heads x 300 rows = 10 tiles, each cut in sixteen (150 slots, over the first call's leftovers)
     cases = [(11, 1, 24, 700, 12900, 12850), (12, 1, 5, 300, 19300, 19300)]
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     data = []

@@ -54,7 +54,9 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     tiles that do not fill a round of whole tiles are cut into s = round(3*n_cu/rem) key ranges,
     at least 2 and at most min(16, nt // 100, n_v // 512, 1 + (9*n_cu//4) // rem) with nt the key
     tiles (of 64) of a whole sweep, lowered until the last range is not empty; uncut if that leaves
-    less than 2.  A range holds ceil(n_v / s) keys rounded up to a multiple of 64."""
+    less than 2.  A launch of fewer tiles than compute units is cut so that one round of parts fills
+    the machine instead: s = n_cu // n_tiles under the same caps except nt // 100.  A range holds
+    ceil(n_v / s) keys rounded up to a multiple of 64."""
     plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
     if d != 128 or n_v <= 0 or BH * Sq <= 0:
         return plan
@@ -68,8 +70,12 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     def keys(s):
         return -(-(-(-n_v // s)) // 64) * 64
 
-    s_max = min(16, nt // 100, n_v // 512, 1 + (9 * n_cu // 4) // rem)
-    s = min(max((6 * n_cu + rem) // (2 * rem), 2), s_max)
+    if tiles < n_cu:                                  # a launch that does not fill one round: one round of parts
+        s_max = min(16, n_v // 512, 1 + (9 * n_cu // 4) // rem)
+        s = min(n_cu // rem, s_max)
+    else:
+        s_max = min(16, nt // 100, n_v // 512, 1 + (9 * n_cu // 4) // rem)
+        s = min(max((6 * n_cu + rem) // (2 * rem), 2), s_max)
     while s >= 2 and (s - 1) * keys(s) >= n_v:
         s -= 1
     if s >= 2:
