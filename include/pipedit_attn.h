@@ -3,7 +3,7 @@
  *
  * C ABI.  Every pointer is a DEVICE pointer unless the comment says "host".
  * The caller owns every tensor.  The library itself keeps one device workspace
- * per (device, stream) for the d = 128 attention kernel: its work counters and
+ * per (device, stream) for the attention kernel: its work counters and
  * the key-range partials of cut query tiles (see pda_attn_tail_plan).  It is
  * allocated once, the first time that kernel is launched on the stream, with
  * the largest size any launch can need
@@ -125,7 +125,7 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
                          int64_t kv_valid_len, int64_t q_offset, void* stream);
 
 /*
- * How a d = 128 attention launch over B*H (batch, head) pairs is cut into work items (host only;
+ * How an attention launch over B*H (batch, head) pairs is cut into work items (host only;
  * every pointer below is a HOST pointer; no device work).  The kernel takes 256-row query tiles,
  * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles
  * (in (batch, head, query tile) order: the partly filled last round; all tiles of a launch
@@ -136,17 +136,17 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
  * the others.  n_cu: compute units of the device (0 = ask the current device).  Outputs (any may
  * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_keys, and
  * workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32 out; never more
- * than 9/4 per compute unit).  d = 64 launches and empty key sets are never cut.
+ * than 9/4 per compute unit; a d = 64 launch fills half of each slot).  Empty key sets are never cut.
  */
 int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
                        int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_keys, int64_t* workspace_slots);
 
 /*
- * Testing aid: pda_attn_fwd (no q_offset) with an explicit choice of kernel for d = 128.
+ * Testing aid: pda_attn_fwd (no q_offset) with an explicit choice of kernel.
  * variant 0 = what pda_attn_fwd runs; 1, 2 = two plain reference tilings of the same MFMA
  * formulation (128 and 256 query rows per workgroup, register-staged double buffering, running
  * max); 3 = variant 0 with its second, running-max sweep forced on every work item.  All compute
- * the same function to rounding.  d = 64 ignores the variant.
+ * the same function to rounding.
  */
 int pda_attn_fwd_variant(const void* q, const void* k, const void* v, float* out, float* lse,
                          int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
@@ -155,7 +155,7 @@ int pda_attn_fwd_variant(const void* q, const void* k, const void* v, float* out
 /*
  * pda_attn_fwd with a bf16 output, for results that go straight on to the next projection and not
  * through pda_attn_merge (which takes fp32 partials): out is [B,H,Sq,d] bf16, rounded to nearest
- * even from the fp32 result; lse stays fp32.  d must be 128.  Everything else as pda_attn_fwd.
+ * even from the fp32 result; lse stays fp32.  Everything else as pda_attn_fwd.
  */
 int pda_attn_fwd_bf16out(const void* q, const void* k, const void* v, void* out, float* lse,
                          int B, int H, int64_t Sq, int64_t Skv, int d, float scale,

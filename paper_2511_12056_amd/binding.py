@@ -175,7 +175,7 @@ def attn_tail_plan(B: int, H: int, Sq: int, kv_valid_len: int, d: int, n_cu: int
 
 
 def attn_fwd_bf16out(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None, stream=None):
-    """pda_attn_fwd_bf16out: as attn_fwd with out [B,H,Sq,d] in bf16 (d = 128)."""
+    """pda_attn_fwd_bf16out: as attn_fwd with out [B,H,Sq,d] in bf16."""
     import torch
     B, H, Sq, d = q.shape
     Skv = k.shape[2]

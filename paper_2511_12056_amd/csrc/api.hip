@@ -376,7 +376,6 @@ int pda_attn_fwd_bf16out(const void* q, const void* k, const void* v, void* out,
                          int64_t kv_valid_len, void* stream) {
     int rc = check_attn_args(q, k, v, static_cast<const float*>(out), lse, B, H, Sq, Skv, d, scale, kv_valid_len);
     if (rc != PDA_OK) return rc;
-    if (d != 128) return fail(PDA_ERR_UNSUPPORTED, "a bf16 output needs d = 128 (got %d)", d);
     if (B == 0 || H == 0 || Sq == 0) return PDA_OK;
     return launch_checked(q, k, v, static_cast<float*>(out), lse, B, H, Sq, d, compact_strides(H, Sq, Skv, d),
                           scale, kv_valid_len, static_cast<hipStream_t>(stream), 0, false, true, WS_CACHED);

@@ -314,17 +314,18 @@ hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, floa
         hipLaunchKernelGGL(attn_empty_kernel, grid, dim3(256), 0, st, p, D);
         return hipGetLastError();
     }
-    if (D == 64) return launch_variant<64, 1, 4, 64, 2>(p, BH, st);
     if (p.out_bf16 && variant != 3) variant = 0;                       // only the software-pipelined kernel writes bf16
     switch (variant) {
-        case 1:  return launch_variant<128, 1, 4, 64, 2>(p, BH, st);   // reference tiling, M=128, two workgroups per CU
-        case 2:  return launch_variant<128, 1, 8, 64, 1>(p, BH, st);   // reference tiling, M=256, two waves per SIMD
+        case 1:                                                        // reference tiling, M=128, two workgroups per CU
+            return D == 64 ? launch_variant<64, 1, 4, 64, 2>(p, BH, st) : launch_variant<128, 1, 4, 64, 2>(p, BH, st);
+        case 2:                                                        // reference tiling, M=256, two waves per SIMD
+            return D == 64 ? launch_variant<64, 1, 8, 64, 1>(p, BH, st) : launch_variant<128, 1, 8, 64, 1>(p, BH, st);
         case 3: {                                                      // software-pipelined kernel, second sweep forced
             AttnParams r = p;
             r.redo_always = 1;
-            return launch_attn_fwd_sp(r, BH, ws, ws_slots, st);
+            return launch_attn_fwd_sp(r, BH, D, ws, ws_slots, st);
         }
-        default: return launch_attn_fwd_sp(p, BH, ws, ws_slots, st);                 // software-pipelined kernel
+        default: return launch_attn_fwd_sp(p, BH, D, ws, ws_slots, st);              // software-pipelined kernel
     }
 }
 

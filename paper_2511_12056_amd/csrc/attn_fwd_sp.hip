@@ -68,8 +68,9 @@ __device__ __forceinline__ void lds_dma16_at(const void* sbase, unsigned voff, u
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N == 8 || N == 16 || N == 0, "add the literal below");
+    static_assert(N == 4 || N == 8 || N == 16 || N == 0, "add the literal below");
     if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 }
@@ -77,22 +78,34 @@ __device__ __forceinline__ void wait_vmcnt() {
 // BASE2: the scores are already in units of log2 (the caller folded scale*log2(e) into Q), so the
 // weights are 2^(q.k) and the first sweep needs no arithmetic before the exponential at all: the
 // score accumulators start from minus the row's reference instead of from zero.
-template <int NQ, bool BASE2>
+// Row-dependent XOR applied to the index of a row's 16-byte granules in an LDS tile, chosen so that
+// the operand reads are free of bank conflicts (64 banks of 4 bytes).  With 256-byte rows (d = 128)
+// every row starts at bank 0: the K reads (16 rows, one granule each) need 16 different granules,
+// the transposing V reads (4 rows, 4 granules each) 4 different groups of 4.  With 128-byte rows
+// (d = 64) even and odd rows already lie in different halves of the banks, so the XOR is taken
+// from the row index without its lowest bit.
+template <int D>
+__device__ __forceinline__ constexpr int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D>
+__device__ __forceinline__ constexpr int swz_v(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+
+template <int D, int NQ, bool BASE2>
 __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnParams p) {
-    constexpr int D = 128;
+    static_assert(D == 128 || D == 64, "head dimension");
     constexpr int NW = 8 / NQ;            // wavefronts
     constexpr int BN = 64;
     constexpr int M = 256;
-    constexpr int G = D / 8;              // 16
+    constexpr int G = D / 8;              // 16-byte granules per row: 16 (d = 128) or 8
     constexpr int NKB = BN / 32;          // 2
-    constexpr int NKK = D / 16;           // 8
-    constexpr int NDB = D / 32;           // 4
-    constexpr int TILE = BN * D * 2;      // 16 KB
+    constexpr int NKK = D / 16;           // 8 or 4
+    constexpr int NDB = D / 32;           // 4 or 2
+    constexpr int TILE = BN * D * 2;      // 16 KB or 8 KB
     constexpr int NBUF = 4;
     constexpr int K_BASE = 0, V_BASE = NBUF * TILE;       // LDS byte offsets
-    constexpr int CHUNKS = TILE / 1024;   // 16 DMA chunks of 1 KB per tile
-    constexpr int CPW = CHUNKS / NW;      // per wavefront: 2 or 4
-    constexpr int RPC = 1024 / (D * 2);   // 4 rows per chunk
+    constexpr int CHUNKS = TILE / 1024;   // DMA chunks of 1 KB per tile: 16 or 8
+    constexpr int CPW = CHUNKS / NW;      // per wavefront: 2 (4 with NQ = 2), or 1 for d = 64
+    constexpr int RPC = 1024 / (D * 2);   // rows per chunk: 4 or 8
+    static_assert(CPW >= 1, "every wavefront fetches at least one chunk of a tile");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int next_item;
@@ -157,12 +170,12 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     const unsigned lds0 = (unsigned)(uintptr_t)(LDS_PTR(const void))smem;
 
     // ---- tile DMA: wavefront w fetches the 1 KB chunks w, w+NW, ... of a tile (4 key rows each).
-    // Lane -> (row, granule to fetch); with this assignment row % 16 does not depend on the chunk
+    // Lane -> (row, granule to fetch); with this assignment row % 32 does not depend on the chunk
     // number, so one per-lane offset serves all of a wavefront's chunks.
     const int ld_row0 = wave * RPC + lane / G;        // row of chunk 0; chunk j adds j*NW*RPC
     const int ld_gp = lane % G;                       // granule position the lane's data lands on
-    const unsigned ld_offk = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ (ld_row0 & (G - 1))) * 16);
-    const unsigned ld_offv = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ ((ld_row0 & 3) << 2)) * 16);
+    const unsigned ld_offk = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ swz_k<D>(ld_row0)) * 16);
+    const unsigned ld_offv = (unsigned)(ld_row0 * D * 2 + (ld_gp ^ swz_v<D>(ld_row0)) * 16);
     // chunk j (0..CPW-1) of this wavefront's share of a tile
     auto issue_chunk = [&](const __bf16* base, unsigned off0, unsigned lds_tile, int tile, int j) {
         const unsigned dst = lds0 + lds_tile + wave * 1024 + j * (NW * 1024);
@@ -203,10 +216,10 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     }
 
     // ---- per-lane LDS operand addresses (loop invariant; buffer and block offsets are immediates)
-    // K operand: row kb*32+li, granule (2kk+lh) ^ (li % 16)
+    // K operand: row kb*32+li, granule (2kk+lh) ^ swz_k(li)
     LDS_PTR(const unsigned char) k_ptr[NKK];
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) k_ptr[kk] = (LDS_PTR(const unsigned char))smem + (K_BASE + li * (D * 2) + (((2 * kk + lh) ^ (li & (G - 1))) * 16));
+    for (int kk = 0; kk < NKK; ++kk) k_ptr[kk] = (LDS_PTR(const unsigned char))smem + (K_BASE + li * (D * 2) + (((2 * kk + lh) ^ swz_k<D>(li)) * 16));
     // V^T operand through the transposing read: within a 16-lane block, lane t supplies the address
     // of 4 consecutive columns (t%4) of key row (t/4) and receives column t of those 4 rows.
     const int t16 = lane & 15;
@@ -214,7 +227,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     LDS_PTR(const unsigned char) v_ptr[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
-        const int g = (db * 4 + 2 * (li >> 4) + ((t16 & 3) >> 1)) ^ ((v_key_in & 3) << 2);
+        const int g = (db * 4 + 2 * (li >> 4) + ((t16 & 3) >> 1)) ^ swz_v<D>(v_key_in);
         v_ptr[db] = (LDS_PTR(const unsigned char))smem + (V_BASE + v_key_in * (D * 2) + g * 16 + (t16 & 1) * 8);
     }
 
@@ -223,7 +236,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     f32x16 nref[NQ];                                   // BASE2, first sweep: minus the row's reference, as an accumulator seed
     f32x16 s_a[NQ][NKB], s_b[NQ][NKB];                 // scores of two consecutive tiles, alternating roles
     // Packed bf16 P (MFMA operand order).  One buffer serves two consecutive tiles: group (kb,u) of
-    // tile t-1 is consumed by the PV MFMAs of slots 4(2kb+u)..+3, before the softmax of tile t writes it.
+    // tile t-1 is consumed by the PV MFMAs of slots (d/32)(2kb+u) .. +d/32-1, before the softmax of tile t writes it.
     unsigned p_io[NQ][NKB][2][4];
     const float c = BASE2 ? 1.0f : p.scale_log2e;   // > 0 (the host substitutes a tiny positive value for scale 0)
 
@@ -324,10 +337,11 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
 
         // One iteration; TB = t % 4 fixes every LDS buffer offset at compile time.
         //   s_c: scores of tile t (in, overwritten by its probabilities)   s_n: scores of tile t+1 (out)
-        // Slot i (0..31) = the MFMAs fed by operand fragment i (PV fragments 0..15, then QK fragments
-        // 0..15; NQ MFMAs each), the LDS reads of fragment i+PF, and slice i of the softmax VALU work:
-        // slices 0-3 the row max, 4-5 the reference / rescale factors, 6-31 the 32 exponentials with
-        // their packing to bf16 and the row sum.
+        // Slot i (0..N_FR-1; N_FR = 32 for d = 128, 16 for d = 64) = the MFMAs fed by operand fragment
+        // i (first the PV fragments, then as many QK fragments; NQ MFMAs each), the LDS reads of
+        // fragment i+PF, and slice i of the softmax VALU work: slices 0-3 the row max, 4-5 the
+        // reference / rescale factors, the others the 32 exponentials with their packing to bf16 and
+        // the row sum.
         auto iteration = [&](auto tb_c, int t, f32x16 (&s_c)[NQ][NKB], f32x16 (&s_n)[NQ][NKB]) {
             constexpr int TB = decltype(tb_c)::value;
             constexpr int KN = (TB + 1) % NBUF;           // buffer of K tile t+1
@@ -352,13 +366,13 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             v_dma += BN * D;
             constexpr int N_PV = NKB * 2 * NDB, N_QK = NKK * NKB, N_FR = N_PV + N_QK;
             constexpr int PF = 3, RING = 4;
-            static_assert(N_FR == 32, "slot plan below is written for d = 128 and 64-key tiles");
+            static_assert(N_FR == 32 || N_FR == 16, "slot plan below is written for 64-key tiles and d = 128 or 64");
             bf16x8 frag[RING];
 
             auto load_frag = [&](auto idx) {
                 constexpr int i = decltype(idx)::value;
                 if constexpr (i < N_PV) {
-                    constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
+                    constexpr int kb = i / (2 * NDB), u = (i / NDB) % 2, db = i % NDB;
                     constexpr int off0 = VP * TILE + (kb * 32 + u * 16) * (D * 2);
                     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0));
                     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(v_ptr[db] + off0 + 8 * (D * 2)));
@@ -373,7 +387,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
             auto do_mfma = [&](auto idx, auto nq_c) {
                 constexpr int i = decltype(idx)::value, nq = decltype(nq_c)::value;
                 if constexpr (i < N_PV) {
-                    constexpr int kb = i / 8, u = (i / 4) % 2, db = i % 4;
+                    constexpr int kb = i / (2 * NDB), u = (i / NDB) % 2, db = i % NDB;
                     const u32x4 pv = {p_io[nq][kb][u][0], p_io[nq][kb][u][1], p_io[nq][kb][u][2], p_io[nq][kb][u][3]};
                     o_acc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i % RING], __builtin_bit_cast(bf16x8, pv),
                                                                             o_acc[nq][db], 0, 0, 0);
@@ -398,14 +412,15 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
                 mx2[nq] = s_c[nq][0][1];
                 mc_new[nq] = SAFE ? 0.f : mc_run[nq]; alpha[nq] = 1.f; lsum[nq] = 0.f; lsum2[nq] = 0.f;
             }
-            // Elements of the lane's 32 scores handled by exponential slot k (0..25): [e_lo(k), e_lo(k+1)).
+            // Elements of the lane's 32 scores handled by exponential slot k (0..NX-1): [e_lo(k), e_lo(k+1)).
             // The work on an element is spread over consecutive slots so that no instruction needs a
             // result produced in its own slot: slot k-1 forms z = s*c - m, slot k takes exp2(z), slot k+1
             // adds it to the row sum and, once both halves of a pair exist, packs the pair to bf16.
-            // SAFE: slots 0-3 row max, 4-5 reference and rescale factor, 6-31 exponentials.  Otherwise the
+            // SAFE: slots 0-3 row max, 4-5 reference and rescale factor, 6.. exponentials.  Otherwise the
             // exponentials start at slot 3 (not earlier: the packed pair q of this tile may replace that of
-            // the previous tile only after the PV MFMAs of slots 0..3, 4..7, ... have read its group).
-            constexpr int X0 = SAFE ? 6 : 3, NX = 32 - X0;
+            // the previous tile only after the PV MFMAs of its group, which come d/32 slots per group in
+            // the first half of the slots, have read it).
+            constexpr int X0 = SAFE ? 6 : 3, NX = N_FR - X0;
             auto e_lo = [](int k) constexpr { return k <= 0 ? 0 : (k >= NX ? 32 : k * 32 / NX); };
             auto fma_of = [&](auto kc, auto nq_c) {
                 constexpr int k = decltype(kc)::value, nq = decltype(nq_c)::value;
@@ -523,13 +538,16 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         };
 
         // The loop runs over tiles 0 .. nt (the extra one only completes PV(nt-1): its scores are all
-        // hidden, so its probabilities are zero), rounded up to a multiple of four so that buffer
-        // offsets are immediates and the score / probability registers alternate roles without copies.
-        const int t_end = (nt + 4) & ~3;
-        for (int t = 0; t < t_end; t += 4) {
+        // hidden, so its probabilities are zero), unrolled by four so that buffer offsets are
+        // immediates and the score / probability registers alternate roles without copies.
+        // (the loop is left right after iteration nt, wherever in the group of four that falls)
+        for (int t = 0; t <= nt; t += 4) {
             iteration(std::integral_constant<int, 0>{}, t, s_a, s_b);
+            if (t == nt) break;
             iteration(std::integral_constant<int, 1>{}, t + 1, s_b, s_a);
+            if (t + 1 == nt) break;
             iteration(std::integral_constant<int, 2>{}, t + 2, s_a, s_b);
+            if (t + 2 == nt) break;
             iteration(std::integral_constant<int, 3>{}, t + 3, s_b, s_a);
         }
         wait_vmcnt<0>();        // no DMA may outlive the workgroup's LDS
@@ -564,12 +582,16 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
         if (__builtin_amdgcn_readfirstlane(any)) sweep(std::true_type{});
     }
 
-    // ---- epilogue: normalise, write out and lse
+    // ---- epilogue: normalise, write out and lse.  The lane's row is formed from a copy of its index
+    // that the compiler cannot trace back, or it would form the store addresses before the sweep and
+    // carry them through it in registers the loop has no room for.
+    int li_e = li;
+    asm volatile("" : "+v"(li_e));
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         const float l_tot = pair_sum(l_run[nq]);
         const float inv = 1.0f / l_tot;
-        const int64_t row = q_row0 + nq * 32 + li;
+        const int64_t row = q_row0 + nq * 32 + li_e;
         if (row < Sq) {
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
@@ -602,13 +624,15 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
 }
 
 // Folds the key-range partials of the cut tiles into out/lse (in place): per row,
-// L = ln sum_p exp(lse_p), out = sum_p exp(lse_p - L) out_p.  One 32-lane group per row (d = 128),
-// so a row's lse is read by all its lanes before one of them overwrites it.
+// L = ln sum_p exp(lse_p), out = sum_p exp(lse_p - L) out_p.  One group of d/4 lanes (half or a
+// quarter of a wavefront) per row, so a row's lse is read by all its lanes before one of them
+// overwrites it.
+template <int D>
 __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int n_tail) {
-    constexpr int D = 128, M = 256;
-    const int tile = p.n_full + blockIdx.x / (M / 8);
-    const int r_in = (blockIdx.x % (M / 8)) * 8 + (threadIdx.x >> 5);
-    const int c4 = threadIdx.x & 31;
+    constexpr int M = 256, LPR = D / 4, RPB = 256 / LPR;      // lanes per row, rows per workgroup
+    const int tile = p.n_full + blockIdx.x / (M / RPB);
+    const int r_in = (blockIdx.x % (M / RPB)) * RPB + (threadIdx.x / LPR);
+    const int c4 = threadIdx.x % LPR;
     const int bh = tile / p.tiles_per_head;
     const int q_tile = tile - bh * p.tiles_per_head;
     const int b = bh / p.Hg, h = bh - b * p.Hg;
@@ -651,11 +675,11 @@ __global__ __launch_bounds__(256) void tail_merge_kernel(const AttnParams p, int
     if (c4 == 0) *lp = m + __logf(tot);
 }
 
-template <int NQ, bool BASE2>
+template <int D, int NQ, bool BASE2>
 static hipError_t launch_sp(AttnParams p, int BH, float* ws, int64_t ws_slots, hipStream_t st) {
-    constexpr int smem = 2 * 4 * 64 * 128 * 2;      // 128 KB
-    constexpr int M = 256, D = 128;
-    auto kern = attn_fwd_sp_kernel<NQ, BASE2>;
+    constexpr int smem = 2 * 4 * 64 * D * 2;        // 128 KB (d = 128) or 64 KB
+    constexpr int M = 256;
+    auto kern = attn_fwd_sp_kernel<D, NQ, BASE2>;
     static KernelSetup setup;
     int n_cu = 0;
     {
@@ -680,12 +704,14 @@ static hipError_t launch_sp(AttnParams p, int BH, float* ws, int64_t ws_slots, h
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512 / NQ), smem, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || t.split <= 1) return e;
-    hipLaunchKernelGGL(tail_merge_kernel, dim3((unsigned)(t.n_cut * (M / 8))), dim3(256), 0, st, p, (int)t.n_cut);
+    hipLaunchKernelGGL(tail_merge_kernel<D>, dim3((unsigned)(t.n_cut * (M / (1024 / D)))), dim3(256), 0, st, p, (int)t.n_cut);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, float* ws, int64_t ws_slots, hipStream_t st) {
-    return p.base2 ? launch_sp<1, true>(p, BH, ws, ws_slots, st) : launch_sp<1, false>(p, BH, ws, ws_slots, st);
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int D, float* ws, int64_t ws_slots, hipStream_t st) {
+    if (D == 64)
+        return p.base2 ? launch_sp<64, 1, true>(p, BH, ws, ws_slots, st) : launch_sp<64, 1, false>(p, BH, ws, ws_slots, st);
+    return p.base2 ? launch_sp<128, 1, true>(p, BH, ws, ws_slots, st) : launch_sp<128, 1, false>(p, BH, ws, ws_slots, st);
 }
 
 }  // namespace pda

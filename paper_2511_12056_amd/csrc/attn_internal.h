@@ -143,10 +143,10 @@ inline int64_t max_tail_slots(int n_cu, bool out_bf16) {
 hipError_t launch_attn_fwd(const AttnParams& p, int BH, int D, int variant, float* ws, int64_t ws_slots, hipStream_t st);
 
 // Software-pipelined kernel for d = 128 (attn_fwd_sp.hip); p.n_v >= 1, p.scale_log2e > 0.
-hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, float* ws, int64_t ws_slots, hipStream_t st);
+hipError_t launch_attn_fwd_sp(const AttnParams& p, int BH, int D, float* ws, int64_t ws_slots, hipStream_t st);
 
 // Does this (d, variant, valid key count) take the software-pipelined kernel (and so possibly a workspace)?
-inline bool uses_sp_kernel(int D, int variant, int64_t n_v) { return D == 128 && n_v > 0 && (variant == 0 || variant == 3); }
+inline bool uses_sp_kernel(int D, int variant, int64_t n_v) { return (D == 128 || D == 64) && n_v > 0 && (variant == 0 || variant == 3); }
 
 // CU count of the current device (cached per device).
 hipError_t device_cu_count(int* n_cu);

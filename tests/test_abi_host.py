@@ -205,7 +205,7 @@ def test_header_is_plain_c(tmp_path):
 
 def test_bf16out_rejects_bad_arguments(pda):
     f = pda.lib.pda_attn_fwd_bf16out
-    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 64, 1.0, 8, None) == 2 and "d = 128" in pda.last_error()
+    assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 96, 1.0, 8, None) == 2 and "head dim" in pda.last_error()
     assert f(128, 128, 128, 128, 128, 1, 1, 8, 8, 128, 1.0, 9, None) == 1
     assert f(128, 128, 128, None, 128, 1, 1, 8, 8, 128, 1.0, 8, None) == 1
     assert f(None, None, None, None, None, 0, 1, 8, 8, 128, 1.0, 8, None) == 0
@@ -250,8 +250,13 @@ def test_tail_plan_matches_the_rule_restated_in_python(pda):
             pl = pda.attn_tail_plan(1, 1, 256 * t, n_v, 128, 256)
             assert pl["workspace_slots"] <= 576
             assert pl["split"] == 1 or (pl["split"] - 1) * pl["part_keys"] < n_v
-    # d = 64 and an empty key set are never cut
-    assert pda.attn_tail_plan(1, 2, 1024, 1024, 64, 256)["split"] == 1
+    # a launch of fewer tiles than compute units: one head of the 9 600-token clip is 38 tiles, 256 // 38 = 6 ranges each
+    assert pda.attn_tail_plan(1, 1, 9600, 9600, 128, 256) == {
+        "n_tiles": 38, "n_cut": 38, "split": 6, "part_keys": 1600, "workspace_slots": 190}
+    # the tiny workload (d = 64): 8 tiles, 1 024 keys allow two ranges of 512
+    assert pda.attn_tail_plan(1, 2, 1024, 1024, 64, 256) == {
+        "n_tiles": 8, "n_cut": 8, "split": 2, "part_keys": 512, "workspace_slots": 8}
+    # an empty key set is never cut
     assert pda.attn_tail_plan(1, 3, 5000, 0, 128, 256)["n_cut"] == 0
     assert pda.lib.pda_attn_tail_plan(1, 1, 8, 8, 32, 256, None, None, None, None, None) == 2
     assert pda.lib.pda_attn_tail_plan(1, 1, -1, 8, 128, 256, None, None, None, None, None) == 1

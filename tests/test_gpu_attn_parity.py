@@ -41,6 +41,10 @@ def test_c1_tiny_full():
     (1, 1, 257, 129, 128, 65),        # mask hides whole trailing tiles
     (1, 2, 130, 4099, 128, 4097),     # long key axis, short query axis
     (1, 1, 513, 64, 64, 1),           # one valid key
+    (1, 2, 700, 901, 64, 845),        # d = 64: several tiles, masked tail inside the last tile
+    (1, 1, 257, 129, 64, 65),         # d = 64: mask hides whole trailing tiles
+    (1, 1, 1, 1, 64, None),           # d = 64: single query, single key
+    (1, 2, 130, 4099, 64, 4097),      # d = 64: long key axis, short query axis
 ])
 def test_ragged_shapes_and_masks(B, H, Sq, Skv, d, n_v):
     q, k, v = gen_qkv(900 + Sq, B, H, Sq, Skv, d, unit_rms=False)
@@ -50,10 +54,10 @@ def test_ragged_shapes_and_masks(B, H, Sq, Skv, d, n_v):
     assert_close(o, l, ro, rl, f"{(B, H, Sq, Skv, d, n_v)}")
 
 
-@pytest.mark.parametrize("gain", [4.0, 8.0])
-def test_peaked_scores(gain):
+@pytest.mark.parametrize("gain,d", [(4.0, 128), (8.0, 128), (8.0, 64)])
+def test_peaked_scores(gain, d):
     # scores with standard deviation 4-8: outputs are O(1), the running max keeps moving
-    B, H, Sq, Skv, d = 1, 2, 640, 2100, 128
+    B, H, Sq, Skv = 1, 2, 640, 2100
     q, k, v = gen_qkv(77, B, H, Sq, Skv, d, unit_rms=True)
     q = f32_to_bf16_bits(bf16_bits_to_f32(q) * np.float32(gain))
     scale = d ** -0.5
@@ -175,7 +179,8 @@ def test_seeded_shape_sweep():
             assert_close(o, l, ro, rl, f"sweep case {case}")
 
 
-def test_scores_far_above_the_first_tile_take_the_running_max_path():
+@pytest.mark.parametrize("d", [128, 64])
+def test_scores_far_above_the_first_tile_take_the_running_max_path(d):
     """The kernel's first attempt keeps the max of a row's first key tile as its only reference; rows
     whose later scores exceed it by more than ~2^64 (in powers of two) would overflow and must be
     recomputed with the running max.  Keys beyond the first tile score hundreds to thousands above
@@ -184,7 +189,7 @@ def test_scores_far_above_the_first_tile_take_the_running_max_path():
     import paper_2511_12056_amd as pda
     from oracle import attention
     rng = np.random.default_rng(77)
-    B, H, Sq, Skv, d = 1, 3, 600, 1500, 128
+    B, H, Sq, Skv = 1, 3, 600, 1500
     q = rng.standard_normal((B, H, Sq, d)).astype(np.float32)
     k = (rng.standard_normal((B, H, Skv, d)) * 0.01).astype(np.float32)
     v = rng.standard_normal((B, H, Skv, d)).astype(np.float32)
@@ -208,21 +213,23 @@ def test_reference_tilings_and_forced_second_sweep_agree_with_the_oracle():
     import torch
     import paper_2511_12056_amd as pda
     from oracle import attention
-    shapes = [(1, 2, 515, 1100, 1050, 0.09), (2, 1, 300, 4200, 4200, 0.3), (1, 3, 777, 64, 40, 0.0883883),
-              (1, 24, 700, 12900, 12850, 0.0883883)]                # the last one: every tile cut in three
-    for i, (B, H, Sq, Skv, n_v, scale) in enumerate(shapes):
-        qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, 128, unit_rms=bool(i % 2))
+    shapes = [(1, 2, 515, 1100, 1050, 0.09, 128), (2, 1, 300, 4200, 4200, 0.3, 128), (1, 3, 777, 64, 40, 0.0883883, 128),
+              (1, 24, 700, 12900, 12850, 0.0883883, 128),           # every tile cut in three
+              (1, 2, 515, 1100, 1050, 0.125, 64), (1, 24, 700, 12900, 12850, 0.125, 64), (2, 1, 300, 4200, 4200, 0.3, 64)]
+    for i, (B, H, Sq, Skv, n_v, scale, d) in enumerate(shapes):
+        qb, kb, vb = gen_qkv(500 + i, B, H, Sq, Skv, d, unit_rms=bool(i % 2))
         ro, rl = attention(qb, kb, vb, scale, n_v)
         q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
         for variant in (0, 1, 2, 3):
-            out = torch.full((B, H, Sq, 128), float("nan"), device="cuda"); lse = torch.full((B, H, Sq), float("nan"), device="cuda")
+            out = torch.full((B, H, Sq, d), float("nan"), device="cuda"); lse = torch.full((B, H, Sq), float("nan"), device="cuda")
             print("variant", variant, "shape", i, flush=True)
             pda.attn_fwd_variant(q, k, v, out, lse, scale, variant, n_v)
             torch.cuda.synchronize()
             assert_close(out.cpu().numpy(), lse.cpu().numpy(), ro, rl, f"variant {variant} shape {i}")
 
 
-def test_large_finite_values_take_the_running_max_path():
+@pytest.mark.parametrize("d", [128, 64])
+def test_large_finite_values_take_the_running_max_path(d):
     """With the fixed reference of the first sweep the weights may reach 2^64; times finite V entries
     of magnitude up to 2^100 that overflows the output accumulators although every row sum stays in
     range.  Such items must be redone with the running max (weights <= 2^8), where the result is
@@ -231,12 +238,12 @@ def test_large_finite_values_take_the_running_max_path():
     import paper_2511_12056_amd as pda
     from oracle import attention
     rng = np.random.default_rng(99)
-    B, H, Sq, Skv, d = 1, 3, 520, 1300, 128
+    B, H, Sq, Skv = 1, 3, 520, 1300
     q = rng.standard_normal((B, H, Sq, d)).astype(np.float32)
     k = (rng.standard_normal((B, H, Skv, d)) * 0.05).astype(np.float32)
     v = rng.standard_normal((B, H, Skv, d)).astype(np.float32)
-    k[:, 0, 64:] *= 12.0                                   # head 0: scores grow ~40 log2 units after the first tile
-    k[0, 1, 700] = q[0, 1, 9] * 0.45                       # head 1: one key ~50 above everything for query row 9
+    k[:, 0, 64:] *= np.float32(12.0 * (128 / d) ** 0.5)    # head 0: scores grow ~40 log2 units after the first tile
+    k[0, 1, 700] = q[0, 1, 9] * np.float32(0.45 * 128 / d) # head 1: one key ~50 above everything for query row 9
     v[:, 0] *= np.float32(2.0 ** 100)                      # head 0: huge values everywhere
     v[:, 1] *= np.float32(2.0 ** 90)
     v[0, 2, 5::7] *= np.float32(2.0 ** 100)                # head 2: ordinary scores, some huge values (no overflow: weights <= ~2^10)
@@ -270,33 +277,36 @@ def _assert_close_bf16(o16, l, ro, rl, what):
     assert (np.abs(l.astype(np.float64) - rl) / np.maximum(np.abs(rl), 1.0)).max() <= 1e-3, what
 
 
-def test_many_key_ranges_per_cut_tile():
+@pytest.mark.parametrize("d", [128, 64])
+def test_many_key_ranges_per_cut_tile(d):
     """A launch of few tiles over a long key axis cuts every tile into the largest number of key
     ranges (16); fp32 result against the oracle, masked tail inside the last range."""
     import torch
     import paper_2511_12056_amd as pda
     from oracle import attention
     B, H, Sq, Skv, n_v = 1, 3, 600, 102500, 102440
-    plan = pda.attn_tail_plan(B, H, Sq, n_v, 128)
+    plan = pda.attn_tail_plan(B, H, Sq, n_v, d)
     if torch.cuda.get_device_properties(0).multi_processor_count == 256:
         assert plan["split"] == 16 and plan["n_cut"] == 9, plan
-    qb, kb, vb = gen_qkv(4711, B, H, Sq, Skv, 128, unit_rms=True)
-    o, l = _run(qb, kb, vb, 128 ** -0.5, n_v)
-    ro, rl = _oracle(qb, kb, vb, 128 ** -0.5, n_v)
-    assert_close(o, l, ro, rl, "16 key ranges")
+    qb, kb, vb = gen_qkv(4711, B, H, Sq, Skv, d, unit_rms=True)
+    o, l = _run(qb, kb, vb, d ** -0.5, n_v)
+    ro, rl = _oracle(qb, kb, vb, d ** -0.5, n_v)
+    assert_close(o, l, ro, rl, f"16 key ranges, d = {d}")
 
 
-@pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut", [(1, 24, 700, 12900, 12850, True),  # 72 tiles, every one cut in three
-                                                     (1, 3, 600, 102500, 102440, True), # 9 tiles, every one cut in sixteen
-                                                     (1, 4, 16384, 600, 570, False),   # 256 tiles: one full round, none cut
-                                                     (2, 5, 300, 2500, 2500, None)])
-def test_bf16_output_against_the_oracle(B, H, Sq, Skv, n_v, all_cut):
+@pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut,d", [(1, 24, 700, 12900, 12850, True, 128),  # 72 tiles, every one cut in three
+                                                       (1, 3, 600, 102500, 102440, True, 128), # 9 tiles, every one cut in sixteen
+                                                       (1, 4, 16384, 600, 570, False, 128),   # 256 tiles: one full round, none cut
+                                                       (2, 5, 300, 2500, 2500, None, 128),
+                                                       (1, 24, 700, 12900, 12850, True, 64),
+                                                       (1, 4, 16384, 600, 570, False, 64),
+                                                       (2, 5, 300, 2500, 2500, None, 64)])
+def test_bf16_output_against_the_oracle(B, H, Sq, Skv, n_v, all_cut, d):
     """pda_attn_fwd_bf16out element by element against the fp64 oracle (its cut tiles take their own
     path: all parts go through the workspace and the merge pass writes bf16)."""
     import torch
     import paper_2511_12056_amd as pda
     from oracle import attention
-    d = 128
     if all_cut is not None:
         plan = pda.attn_tail_plan(B, H, Sq, n_v, d)
         if plan["n_tiles"] % torch.cuda.get_device_properties(0).multi_processor_count == 0:
@@ -312,15 +322,15 @@ def test_bf16_output_against_the_oracle(B, H, Sq, Skv, n_v, all_cut):
     _assert_close_bf16(o16.float().cpu().numpy(), l16.cpu().numpy(), ro, rl, f"bf16 out {(B, H, Sq, Skv, n_v)}")
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("B,H,Sq,Skv,n_v", [(1, 2, 515, 1100, 1050), (2, 5, 300, 2500, 2500), (1, 3, 5000, 5000, 4990),
                                             (1, 1, 77, 64, 0), (1, 24, 700, 12900, 12850), (2, 3, 300, 40000, 39990)])
-def test_bf16_output_is_the_rounded_fp32_output(B, H, Sq, Skv, n_v):
+def test_bf16_output_is_the_rounded_fp32_output(B, H, Sq, Skv, n_v, d):
     """Same kernels, same arithmetic; only the last store differs (tiles cut into key ranges are
     merged from fp32 partials in both cases).  Hence bit equality with the rounded fp32 result, and
     through it parity with the oracle."""
     import torch
     import paper_2511_12056_amd as pda
-    d = 128
     qb, kb, vb = gen_qkv(300 + H, B, H, Sq, Skv, d, unit_rms=True)
     q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
     o32 = torch.full((B, H, Sq, d), float("nan"), device="cuda"); l32 = torch.full((B, H, Sq), float("nan"), device="cuda")

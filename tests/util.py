@@ -49,7 +49,7 @@ def assert_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
 
 
 def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
-    """Which query tiles a d = 128 attention launch computes as merged key-range partials: the rule
+    """Which query tiles an attention launch (d = 64 or 128) computes as merged key-range partials: the rule
     of pda_attn_tail_plan written out independently.  Tiles of 256 rows; the rem = n_tiles mod n_cu
     tiles that do not fill a round of whole tiles are cut into s = round(3*n_cu/rem) key ranges,
     at least 2 and at most min(16, nt // 100, n_v // 512, 1 + (9*n_cu//4) // rem) with nt the key
@@ -58,7 +58,7 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     the machine instead: s = n_cu // n_tiles under the same caps except nt // 100.  A range holds
     ceil(n_v / s) keys rounded up to a multiple of 64."""
     plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
-    if d != 128 or n_v <= 0 or BH * Sq <= 0:
+    if d not in (64, 128) or n_v <= 0 or BH * Sq <= 0:
         return plan
     tiles = -(-Sq // 256) * BH
     plan["n_tiles"] = tiles
