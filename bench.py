@@ -231,8 +231,23 @@ def next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, t_linear_ms):
     res["attn_base2_scale_folded_into_q_pack"] = {"bound": "mfma", "launch_ms": ms, "flops_per_launch": fl,
                                                   "achieved": fl / (ms * 1e-3) * 1e-12, "peak": PEAK_BF16_TFLOPS,
                                                   "unit": "TFLOP/s", "frac": fl / (ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS,
-                                                  "kernel": "attn_fwd_sp_kernel<1, true> (one 3-head group)"}
+                                                  "kernel": "attn_fwd_sp_kernel<128, 1, true> (one 3-head group)"}
     del xq, q2
+
+    # the d = 64 instance of the attention kernel on a long sequence (the workloads have d = 64 only in
+    # the tiny one): the 544 x 960 token count, 6 heads, inputs = the halves of the workload's vectors
+    S64, h64 = 67576, 6
+    q64, k64, v64 = (t.view(1, H, 2 * S, 64)[:, :h64, :S64].contiguous() for t in (q, k, v))
+    o64 = torch.empty(1, h64, S64, 64, device="cuda")
+    l64 = torch.empty(1, h64, S64, device="cuda")
+    ms = _event_ms(torch, cs, lambda: pda.attn_fwd(q64, k64, v64, o64, l64, 0.125, stream=cs))
+    fl = 4.0 * S64 * S64 * 64 * h64
+    res["attn_d64_6_heads_x_67576"] = {"bound": "alu", "launch_ms": ms, "flops_per_launch": fl,
+                                       "achieved": fl / (ms * 1e-3) * 1e-12, "unit": "TFLOP/s",
+                                       "frac_of_bf16_mfma_peak": fl / (ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS,
+                                       "kernel": "attn_fwd_sp_kernel<64, 1, false>",
+                                       "note": "half the MFMA work per score: bound by the issue of the softmax arithmetic"}
+    del q64, k64, v64, o64, l64
 
     # head-chunk pipeline with the post-processing folded into the hand-off (token-major, final order)
     tok = sink.view(1, S, H, d)
@@ -371,7 +386,7 @@ def main():
                                "c5_720p_split_merge (6 heads: 3 query ranges, 4 key chunks + merge)",
                    "B": w.B, "H": w.H, "d": w.d, "S": w.Sq, "heads_per_group": w.heads_per_group,
                    "seed": w.seed, "flops_per_step": flops_step},
-        "roofline": {"kernel": "attn_fwd_sp_kernel<1, false> (one 3-head group)", "bound": "mfma", "achieved": achieved,
+        "roofline": {"kernel": "attn_fwd_sp_kernel<128, 1, false> (one 3-head group)", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "launch_ms": launch_ms, "flops_per_launch": flops_launch,
                      "traffic": measured_traffic("attn_fwd_sp_kernel_3head_group")},

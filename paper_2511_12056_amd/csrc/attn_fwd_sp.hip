@@ -118,12 +118,19 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     // Persistent workgroups (one per CU) take work items in index order from a device counter: the
     // chip's XCDs run at persistently different speeds (several percent apart under the power
     // limit) and the hardware deals the workgroups of a grid to them round robin, so a grid with
-    // one workgroup per item would end with the slowest XCD while the others idle.
-    for (;;) {
-    if (tid == 0) next_item = atomicAdd(p.counter, 1);
-    __syncthreads();
-    const int item = __builtin_amdgcn_readfirstlane(next_item);
-    __syncthreads();                                   // everyone has read it before the next fetch overwrites it
+    // one workgroup per item would end with the slowest XCD while the others idle.  A launch with no
+    // more items than workgroups needs no counter: workgroup i takes item i and leaves.
+    const bool direct = p.n_items <= (int)gridDim.x;
+    for (int round = 0;; ++round) {
+    int item;
+    if (direct) {
+        item = round == 0 ? (int)blockIdx.x : p.n_items;
+    } else {
+        if (tid == 0) next_item = atomicAdd(p.counter, 1);
+        __syncthreads();
+        item = __builtin_amdgcn_readfirstlane(next_item);
+        __syncthreads();                               // everyone has read it before the next fetch overwrites it
+    }
     if (item >= p.n_items) break;
 
     // ---- work item -> (query tile, head, key range).  Items [0, n_full) are whole tiles; then the
@@ -614,7 +621,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     // The last workgroup to leave puts both counters back to zero for the next launch that uses this
     // workspace (launches sharing a workspace are ordered on one stream).  Every workgroup has made
     // its last fetch before it counts itself out, so nobody fetches after the reset.
-    if (tid == 0) {
+    if (!direct && tid == 0) {
         __threadfence();
         if (atomicAdd(p.counter + 1, 1) == (int)gridDim.x - 1) {
             __hip_atomic_store(p.counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
