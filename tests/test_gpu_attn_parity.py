@@ -154,8 +154,8 @@ def test_seeded_shape_sweep():
     import paper_2511_12056_amd as pda
     from oracle import attention
     rng = np.random.default_rng(20251112)
-    for case in range(18):
-        d = 128 if case % 6 else 64
+    for case in range(24):
+        d = 128 if case % 3 else 64
         B = int(rng.integers(1, 3))
         H = int(rng.integers(1, 6))
         Sq = int(rng.integers(1, 900))
