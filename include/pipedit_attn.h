@@ -129,7 +129,8 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
  * every pointer below is a HOST pointer; no device work).  The kernel takes 256-row query tiles,
  * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles
  * (in (batch, head, query tile) order: the partly filled last round; all tiles of a launch
- * with fewer tiles than compute units) are each computed as `split` (2..16) partial attentions
+ * with fewer tiles than compute units; none where the key ranges would get too short to pay)
+ * are each computed as `split` (2..16) partial attentions
  * over key ranges of part_keys keys and merged with the formula of pda_attn_merge; all other
  * tiles are swept in one pass.  Hence two launches agree bit for bit
  * on every row that lies in an uncut tile of both, and to the rounding of the probabilities on

@@ -67,22 +67,25 @@ struct AttnParams {
     int redo_always;        // software-pipelined kernel: sweep every item a second time with the running max (testing aid)
 };
 
-// Tail plan of the software-pipelined kernel (d = 128, 256-row query tiles, one persistent
+// Tail plan of the software-pipelined kernel (256-row query tiles, one persistent
 // workgroup per CU taking items in order).  Whole tiles are long items (a 119 056-key sweep takes
 // 3 ms), the XCDs run at different speeds, and a launch ends when the last item does; so the
 // `rem` = n_tiles mod n_cu tiles that do not fill a round of whole tiles are cut into `split` key
 // ranges, short items that the workgroups pick up as they run out of whole tiles.  Measured on
-// the device: about three part items per CU balance the end of a launch; parts shorter than about
-// 100 key tiles cost more (prologue, partial store, merge) than they recover, so short sweeps are
-// left uncut.  Rule:
+// the device: about three part items per CU balance the end of a long launch; every part pays a
+// prologue, a partial store and its share of the merge, so parts are kept at 100 key tiles or more
+// (50 where that gives no more than 4 ranges).  Rule:
 //     split = round(3 * n_cu / rem), at least 2, at most the smallest of
-//             16, nt / 100 (nt = key tiles of a whole sweep), n_v / 512,
+//             16, max(nt / 100, min(nt / 50, 4)) (nt = key tiles of a whole sweep), n_v / 512,
 //             1 + (9 * n_cu / 4) / rem   (workspace: the parts beyond the first must fit),
 //     lowered until the last range is not empty; uncut if that leaves less than 2 or rem = 0.
-// A launch with fewer tiles than CUs (one head of a short clip: the unit PipeSP pipelines) would
-// leave CUs without work for its whole duration: its tiles are cut so that one round of parts
-// fills the machine, split = floor(n_cu / n_tiles) under the same caps except nt / 100 (measured:
-// 38 tiles of 150 key tiles, split 6: 0.081 ms instead of 0.181 ms).
+// Where the parts are short and the CUs become free together, parts run in rounds like tiles do,
+// and ONE round of parts is best: split = floor(n_cu / rem) under the same caps except the one on
+// the part length.  That is the plan of a launch with fewer tiles than CUs (one head of a short
+// clip, the unit PipeSP pipelines, would otherwise leave CUs without work for its whole duration;
+// measured: 38 tiles of 150 key tiles, split 6: 0.081 ms instead of 0.181 ms) and of sweeps of
+// under 200 key tiles whose left-over tiles fill at most half the machine (measured: 10 heads x
+// 9 600 tokens, rem = 124: 0.502 / 0.428 / 0.451 / 0.442 ms for split 1 / 2 / 3 / 4).
 // A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
 // the last n_cut of the launch's n_tiles tiles in (batch, head, query tile) order.
 constexpr int kMaxSplit = 16;
@@ -103,12 +106,20 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
     const int64_t rem = t.n_tiles % n_cu;
     if (rem) {
         const int64_t nt = (n_v + 63) / 64;
-        const bool one_round = t.n_tiles < n_cu;
+        // One round of parts (n_cu / rem ranges per tile) where the parts are short and start together:
+        // a launch of fewer tiles than CUs, or sweeps of under 200 key tiles whose left-over tiles
+        // fill at most half the machine.  Otherwise about three rounds of parts, round(3 n_cu / rem),
+        // of at least 100 key tiles each (at least 50 where that gives no more than 4 ranges).
+        const bool one_round = t.n_tiles < n_cu || (nt < 200 && 2 * rem <= n_cu);
         int64_t s_max = kMaxSplit;
-        if (!one_round && nt / 100 < s_max) s_max = nt / 100;
+        if (!one_round) {
+            int64_t by_len = nt / 50 < 4 ? nt / 50 : 4;
+            if (nt / 100 > by_len) by_len = nt / 100;
+            if (by_len < s_max) s_max = by_len;
+        }
         if (n_v / 512 < s_max) s_max = n_v / 512;
         if (1 + max_extra_slots(n_cu) / rem < s_max) s_max = 1 + max_extra_slots(n_cu) / rem;
-        int64_t s = one_round ? n_cu / rem : (6 * (int64_t)n_cu + rem) / (2 * rem);   // fill one round, or round(3 * n_cu / rem)
+        int64_t s = one_round ? n_cu / rem : (6 * (int64_t)n_cu + rem) / (2 * rem);
         if (s < 2 && !one_round) s = 2;
         if (s > s_max) s = s_max;
         while (s >= 2 && (s - 1) * part_keys_for(n_v, (int)s) >= n_v) --s;   // the last range must not be empty

@@ -238,9 +238,14 @@ def test_tail_plan_matches_the_rule_restated_in_python(pda):
     # the workloads: one 3-head group at 720p is 1 398 tiles = 5 x 256 + 118; round(768/118) = 7 ranges, 5 fit the workspace
     assert pda.attn_tail_plan(1, 3, 119056, 119056, 128, 256) == {
         "n_tiles": 1398, "n_cut": 118, "split": 5, "part_keys": 23872, "workspace_slots": 472}
-    # 24 heads x 9 600: 912 tiles = 3 x 256 + 144; sweeps of only 150 key tiles are left uncut
+    # 24 heads x 9 600: 912 tiles = 3 x 256 + 144; sweeps of 150 key tiles allow three ranges of 50
     assert pda.attn_tail_plan(1, 24, 9600, 9600, 128, 256) == {
-        "n_tiles": 912, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
+        "n_tiles": 912, "n_cut": 144, "split": 3, "part_keys": 3200, "workspace_slots": 288}
+    # 10 heads x 9 600: 380 tiles = 256 + 124 short ones: one round of 248 parts
+    assert pda.attn_tail_plan(1, 10, 9600, 9600, 128, 256) == {
+        "n_tiles": 380, "n_cut": 124, "split": 2, "part_keys": 4800, "workspace_slots": 124}
+    # 24 heads x 4 800: 456 tiles = 256 + 200 of 75 key tiles: left uncut
+    assert pda.attn_tail_plan(1, 24, 4800, 4800, 128, 256)["split"] == 1
     # one head group of the 544 x 960 clip: 792 tiles = 3 x 256 + 24, 1 055 key tiles: at most 10 ranges
     assert pda.attn_tail_plan(1, 3, 67576, 67476, 128, 256) == {
         "n_tiles": 792, "n_cut": 24, "split": 10, "part_keys": 6784, "workspace_slots": 216}

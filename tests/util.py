@@ -52,10 +52,11 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     """Which query tiles an attention launch (d = 64 or 128) computes as merged key-range partials: the rule
     of pda_attn_tail_plan written out independently.  Tiles of 256 rows; the rem = n_tiles mod n_cu
     tiles that do not fill a round of whole tiles are cut into s = round(3*n_cu/rem) key ranges,
-    at least 2 and at most min(16, nt // 100, n_v // 512, 1 + (9*n_cu//4) // rem) with nt the key
-    tiles (of 64) of a whole sweep, lowered until the last range is not empty; uncut if that leaves
-    less than 2.  A launch of fewer tiles than compute units is cut so that one round of parts fills
-    the machine instead: s = n_cu // n_tiles under the same caps except nt // 100.  A range holds
+    at least 2 and at most min(16, L, n_v // 512, 1 + (9*n_cu//4) // rem) with nt the key tiles (of
+    64) of a whole sweep and L = max(nt // 100, min(nt // 50, 4)), lowered until the last range is
+    not empty; uncut if that leaves less than 2.  A launch of fewer tiles than compute units, or one
+    with nt < 200 whose left-over tiles fill at most half the machine, is cut so that one round of
+    parts fills the machine instead: s = n_cu // rem under the same caps except L.  A range holds
     ceil(n_v / s) keys rounded up to a multiple of 64."""
     plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
     if d not in (64, 128) or n_v <= 0 or BH * Sq <= 0:
@@ -70,11 +71,12 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     def keys(s):
         return -(-(-(-n_v // s)) // 64) * 64
 
-    if tiles < n_cu:                                  # a launch that does not fill one round: one round of parts
+    if tiles < n_cu or (nt < 200 and 2 * rem <= n_cu):   # short parts that start together: one round of parts
         s_max = min(16, n_v // 512, 1 + (9 * n_cu // 4) // rem)
         s = min(n_cu // rem, s_max)
     else:
-        s_max = min(16, nt // 100, n_v // 512, 1 + (9 * n_cu // 4) // rem)
+        by_len = max(nt // 100, min(nt // 50, 4))
+        s_max = min(16, by_len, n_v // 512, 1 + (9 * n_cu // 4) // rem)
         s = min(max((6 * n_cu + rem) // (2 * rem), 2), s_max)
     while s >= 2 and (s - 1) * keys(s) >= n_v:
         s -= 1
