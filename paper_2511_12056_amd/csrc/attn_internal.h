@@ -49,14 +49,16 @@ struct AttnParams {
     float scale_log2e;      // scale * log2(e)
     // Work items of the software-pipelined kernel, taken in index order by persistent workgroups.
     // Items [0, n_full) are whole 256-row query tiles (tile = item; head = tile / tiles_per_head).
-    // Every later tile is cut into `split` key ranges of part_keys keys, one item each (item =
-    // n_full + part * n_cut + cut tile), so that the end of the launch is made of short items;
+    // Every later tile is cut into `split` key ranges, the first of first_keys keys, the others of
+    // part_keys keys (the last one: what is left), one item each (item = n_full + part * n_cut +
+    // cut tile), so that the end of the launch is made of short items;
     // part 0 writes out/lse, parts >= 1 write normalised partials to part_out/part_lse, which a
     // merge pass folds into out/lse.  split <= 1: no cut.
     int tiles_per_head;
     int n_full;
     int split;
     int64_t part_keys;
+    int64_t first_keys;
     float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
     float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
     int n_cut;              // number of cut tiles (the last n_cut of the launch)
@@ -86,6 +88,14 @@ struct AttnParams {
 // measured: 38 tiles of 150 key tiles, split 6: 0.081 ms instead of 0.181 ms) and of sweeps of
 // under 200 key tiles whose left-over tiles fill at most half the machine (measured: 10 heads x
 // 9 600 tokens, rem = 124: 0.502 / 0.428 / 0.451 / 0.442 ms for split 1 / 2 / 3 / 4).
+// Where the left-over tiles fill more than half the machine and at most three rounds of whole
+// tiles precede them, no equal cut within the workspace balances the end (210 left-over tiles in
+// 3 ranges are 630 parts: 2.5 rounds, which end when 3 would).  Such tiles are cut UNEQUALLY: a
+// long first range of a fraction A of the keys, taken by rem CUs, and split-1 short ranges, which
+// the other n_cu - rem CUs work off meanwhile, k each: k = ceil(rem (split-1) / (n_cu - rem)),
+// A = k / (k + split - 1) (both kinds of CU then finish together), split = 4 after one round of
+// whole tiles, else 3, within the workspace cap and with short ranges of at least 1024 keys
+// (measured, one head at S = 119 056 = 256 + 210 tiles: 5.78 -> 5.47 ms; 5 x 36 000: 2.64 -> 2.55).
 // A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
 // the last n_cut of the launch's n_tiles tiles in (batch, head, query tile) order.
 constexpr int kMaxSplit = 16;
@@ -94,7 +104,8 @@ struct TailPlan {
     int64_t n_tiles;
     int64_t n_cut;          // 0 if no tile is cut
     int split;              // 1 if no tile is cut
-    int64_t part_keys;      // keys per range (multiple of 64); 0 if no tile is cut
+    int64_t part_keys;      // keys of ranges 1 .. split-1 (multiple of 64; the last range holds what is left); 0 if no tile is cut
+    int64_t first_keys;     // keys of range 0 (multiple of 64); equal to part_keys unless the cut is unequal
 };
 inline int64_t max_extra_slots(int n_cu) { return (int64_t)n_cu * 9 / 4; }
 inline int64_t part_keys_for(int64_t n_v, int s) { return ((n_v + s - 1) / s + 63) / 64 * 64; }
@@ -128,6 +139,24 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
     if (t.split > 1) {
         t.n_cut = rem;
         t.part_keys = part_keys_for(n_v, t.split);
+        t.first_keys = t.part_keys;
+    }
+    // unequal cut: many left-over tiles after at most three rounds of whole tiles
+    if (rem && 2 * rem > n_cu && t.n_tiles < 4 * (int64_t)n_cu && t.n_tiles > n_cu) {
+        int64_t s = t.n_tiles < 2 * (int64_t)n_cu ? 4 : 3;
+        if (1 + max_extra_slots(n_cu) / rem < s) s = 1 + max_extra_slots(n_cu) / rem;
+        for (; s >= 2; --s) {
+            const int64_t k = (rem * (s - 1) + (n_cu - rem) - 1) / (n_cu - rem);
+            const int64_t first = ((n_v * k / (k + s - 1) + n_v / 100) / 64 + 1) * 64;
+            if (first >= n_v) continue;
+            const int64_t part = ((n_v - first + (s - 2)) / (s - 1) + 63) / 64 * 64;
+            if (part < 1024 || first + (s - 2) * part >= n_v) continue;    // short ranges too short, or the last one empty
+            t.split = (int)s;
+            t.n_cut = rem;
+            t.first_keys = first;
+            t.part_keys = part;
+            break;
+        }
     }
     return t;
 }

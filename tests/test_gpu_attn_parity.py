@@ -294,6 +294,27 @@ def test_many_key_ranges_per_cut_tile(d):
     assert_close(o, l, ro, rl, f"16 key ranges, d = {d}")
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_unequal_key_ranges(d):
+    """A launch of one round of whole tiles plus many left-over tiles (420 tiles on 256 CUs: 164 left
+    over) cuts those into a long first key range and short others; sampled rows of whole and of cut
+    tiles, with the masked tail inside the last short range, against the oracle."""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention_head
+    B, H, Sq, Skv, n_v = 1, 20, 5200, 13100, 13050
+    plan = pda.attn_tail_plan(B, H, Sq, n_v, d)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert plan["n_cut"] == 164 and plan["split"] == 4 and plan["first_keys"] > 2 * plan["part_keys"], plan
+    qb, kb, vb = gen_qkv(4242, B, H, Sq, Skv, d, unit_rms=True)
+    o, l = _run(qb, kb, vb, d ** -0.5, n_v)
+    rng = np.random.default_rng(3)
+    for h in (0, 7, 12, 13, 19):            # heads 0-11 are whole tiles, head 12 both, heads 13-19 cut (256 CUs)
+        rows = np.unique(np.concatenate([[0, 255, 256, Sq - 1], rng.choice(Sq, size=120, replace=False)]))
+        ro, rl = attention_head(qb[0, h], kb[0, h], vb[0, h], d ** -0.5, n_v, rows=rows)
+        assert_close(o[0, h][rows], l[0, h][rows], ro, rl, f"unequal ranges, d = {d}, head {h}")
+
+
 @pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut,d", [(1, 24, 700, 12900, 12850, True, 128),  # 72 tiles, every one cut in three
                                                        (1, 3, 600, 102500, 102440, True, 128), # 9 tiles, every one cut in sixteen
                                                        (1, 4, 16384, 600, 570, False, 128),   # 256 tiles: one full round, none cut

@@ -57,8 +57,9 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     not empty; uncut if that leaves less than 2.  A launch of fewer tiles than compute units, or one
     with nt < 200 whose left-over tiles fill at most half the machine, is cut so that one round of
     parts fills the machine instead: s = n_cu // rem under the same caps except L.  A range holds
-    ceil(n_v / s) keys rounded up to a multiple of 64."""
-    plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_keys": 0, "workspace_slots": 0}
+    ceil(n_v / s) keys rounded up to a multiple of 64 (first_keys = part_keys), except in the
+    unequal cut described at the end of the function."""
+    plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "first_keys": 0, "part_keys": 0, "workspace_slots": 0}
     if d not in (64, 128) or n_v <= 0 or BH * Sq <= 0:
         return plan
     tiles = -(-Sq // 256) * BH
@@ -81,7 +82,21 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     while s >= 2 and (s - 1) * keys(s) >= n_v:
         s -= 1
     if s >= 2:
-        plan.update(n_cut=rem, split=s, part_keys=keys(s), workspace_slots=rem * (s - 1))
+        plan.update(n_cut=rem, split=s, first_keys=keys(s), part_keys=keys(s), workspace_slots=rem * (s - 1))
+    # Unequal cut where the left-over tiles fill more than half the machine after one to three rounds
+    # of whole tiles: a long first range (a fraction k / (k + s - 1) of the keys plus 1 %, up to the
+    # next multiple of 64) and s - 1 short ones of at least 1024 keys, k = ceil(rem (s-1) / (n_cu - rem));
+    # s = 4 after one round of whole tiles, else 3, within the workspace cap, lowered until it fits.
+    if 2 * rem > n_cu and n_cu < tiles < 4 * n_cu:
+        s = min(4 if tiles < 2 * n_cu else 3, 1 + (9 * n_cu // 4) // rem)
+        while s >= 2:
+            k = -(-rem * (s - 1) // (n_cu - rem))
+            first = ((n_v * k // (k + s - 1) + n_v // 100) // 64 + 1) * 64
+            part = -(-(-(-(n_v - first) // (s - 1))) // 64) * 64 if first < n_v else 0
+            if first < n_v and part >= 1024 and first + (s - 2) * part < n_v:
+                plan.update(n_cut=rem, split=s, first_keys=first, part_keys=part, workspace_slots=rem * (s - 1))
+                break
+            s -= 1
     return plan
 
 
