@@ -294,3 +294,34 @@ def test_launches_on_two_streams_do_not_share_a_workspace():
     torch.cuda.synchronize()
     for (_, _, _, _, ref, rlse, out, lse) in data:
         assert torch.equal(out, ref) and torch.equal(lse, rlse)
+
+
+def test_headchunk_pipeline_captured_into_a_graph():
+    """The head-by-head pipeline (two streams, one event per group) captured into a HIP graph after
+    one eager call (which allocates the compute stream's workspace); the drain stream is joined
+    back inside the capture.  Every replay, with eager pipelines and synchronisations in between,
+    reproduces the eager result bit for bit in out, lse and the hand-off buffer."""
+    import torch
+    import paper_2511_12056_amd as pda
+    B, H, S = 1, 6, 2100
+    scale = 128 ** -0.5
+    qb, kb, vb = gen_qkv(55, B, H, S, S, 128, unit_rms=True)
+    q, k, v = to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb)
+    ref = torch.empty(B, H, S, 128, device="cuda"); rlse = torch.empty(B, H, S, device="cuda"); rsink = torch.empty_like(ref)
+    out = torch.empty_like(ref); lse = torch.empty_like(rlse); sink = torch.empty_like(ref)
+    cs, ds = torch.cuda.Stream(), torch.cuda.Stream()
+    pda.headchunk_run(q, k, v, ref, rlse, scale, 1, cs, ds, sink=rsink)
+    cs.synchronize(); ds.synchronize()
+    assert torch.equal(ref, rsink)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=cs):
+        pda.headchunk_run(q, k, v, out, lse, scale, 1, cs, ds, sink=sink)
+        cs.wait_stream(ds)
+    for rep in range(3):
+        out.fill_(float("nan")); sink.fill_(float("nan")); lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref) and torch.equal(sink, rsink) and torch.equal(lse, rlse), rep
+        pda.headchunk_run(q, k, v, out, lse, scale, 2, cs, ds, sink=sink)      # eager work between the replays, other grouping
+        cs.synchronize(); ds.synchronize()
