@@ -222,6 +222,9 @@ int pda_attn_merge(const float* const* partials, const float* const* lses, int n
  * is non-NULL the call synchronises both streams before returning; otherwise
  * it returns after enqueueing and the caller must wait on BOTH streams.
  * The two streams must differ.  Events are created and destroyed inside the call.
+ * The untimed form may be captured into a HIP graph once the compute stream has run an
+ * attention launch outside the capture (its workspace exists then): begin the capture on the
+ * compute stream, call, make the compute stream wait for the drain stream, end the capture.
  */
 int pda_headchunk_run(const void* q, const void* k, const void* v, float* out, float* lse,
                       int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
