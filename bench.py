@@ -416,6 +416,12 @@ def main():
                                       "frac_of_loop_with_reads": achieved / ladder["plus_operand_reads_from_lds"],
                                       "what": "MFMA-only loop on Q's values, then with the softmax arithmetic and the LDS operand "
                                               "reads of the attention loop added at the kernel's density (pda_probe_loop_rate)"}
+    # same-run reference for the HBM-bound kernels: torch's device-to-device copy of the full output tensor
+    with torch.cuda.stream(cs):
+        ms_t = _event_ms(torch, cs, lambda: sink.copy_(out))
+    copy_bytes = 2.0 * out.numel() * 4
+    res["roofline_merge"]["same_run_copy"] = {"torch_copy_GBs": copy_bytes / (ms_t * 1e-3) * 1e-9, "bytes": copy_bytes,
+                                              "what": "torch fp32 copy_ of the [24, 119056, 128] output on the compute stream"}
     if not args.no_next_rows:
         del qr, kc, kc_out, outq, lseq
         res["next_rows"] = next_rows(pda, torch, w, q, k, v, out, lse, sink, cs, ds, args.t_linear_ms)
