@@ -416,6 +416,11 @@ def main():
                                       "frac_of_loop_with_reads": achieved / ladder["plus_operand_reads_from_lds"],
                                       "what": "MFMA-only loop on Q's values, then with the softmax arithmetic and the LDS operand "
                                               "reads of the attention loop added at the kernel's density (pda_probe_loop_rate)"}
+    # the pipeline against ONE launch over all 24 heads (no groups, no hand-off): what the granularity costs
+    with torch.cuda.stream(cs):
+        ms_one = _event_ms(torch, cs, lambda: pda.attn_fwd(q, k, v, out, lse, w.scale, stream=cs), iters=2)
+    res["pipeline"]["single_launch_all_heads_ms"] = ms_one
+    res["pipeline"]["pipeline_over_single_launch"] = res["pipeline"]["total_ms_mean"] / ms_one
     # same-run reference for the HBM-bound kernels: torch's device-to-device copy of the full output tensor
     with torch.cuda.stream(cs):
         ms_t = _event_ms(torch, cs, lambda: sink.copy_(out))
