@@ -130,20 +130,22 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
  * one workgroup per compute unit at a time, so tiles run in rounds of n_cu.  The last n_cut tiles
  * (in (batch, head, query tile) order: the partly filled last round; all tiles of a launch
  * with fewer tiles than compute units; none where the key ranges would get too short to pay)
- * are each computed as `split` (2..16) partial attentions over consecutive key ranges (the
- * first of first_keys keys, the others of part_keys keys, the last one what is left; equal
- * ranges unless many left-over tiles follow few rounds of whole tiles, where a long first range
- * and short others balance the end better) and merged with the formula of pda_attn_merge; all other
- * tiles are swept in one pass.  Hence two launches agree bit for bit
+ * are each computed as `split` (2..PDA_MAX_KEY_RANGES) partial attentions over consecutive key
+ * ranges (range j = keys [part_offsets[j], part_offsets[j+1]), boundaries at multiples of 64;
+ * equal ranges, or a long first one and short others where many left-over tiles follow few rounds
+ * of whole tiles, or decreasing ones after many rounds, whichever balances the end of the launch
+ * better) and merged with the formula of pda_attn_merge; all other tiles are swept in one pass.  Hence two launches agree bit for bit
  * on every row that lies in an uncut tile of both, and to the rounding of the probabilities on
  * the others.  n_cu: compute units of the device (0 = ask the current device).  Outputs (any may
- * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_keys, first_keys, and
+ * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_offsets (HOST
+ * array of PDA_MAX_KEY_RANGES + 1 values: part_offsets[0] = 0, entries from index split on are
+ * kv_valid_len), and
  * workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32 out; never more
  * than 9/4 per compute unit; a d = 64 launch fills half of each slot).  Empty key sets are never cut.
  */
+#define PDA_MAX_KEY_RANGES 16
 int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
-                       int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_keys, int64_t* workspace_slots,
-                       int64_t* first_keys);
+                       int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_offsets, int64_t* workspace_slots);
 
 /*
  * Testing aid: pda_attn_fwd (no q_offset) with an explicit choice of kernel.

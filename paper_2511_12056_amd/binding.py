@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libpipedit_attn.so")
 PDA_OK, PDA_ERR_INVALID_ARG, PDA_ERR_UNSUPPORTED, PDA_ERR_HIP, PDA_ERR_NOMEM = 0, 1, 2, 3, 4
 PDA_MAX_PARTIALS = 16
 PDA_NOALLOC_MAX_SLOTS = 576
+PDA_MAX_KEY_RANGES = 16
 PDA_MAX_LOCAL_HEADS = 64
 PDA_SINK_HEAD_MAJOR, PDA_SINK_TOKEN_ARRIVAL, PDA_SINK_TOKEN_FINAL = 0, 1, 2
 
@@ -45,7 +46,7 @@ def _load() -> C.CDLL:
     lib.pda_attn_fwd_variant.argtypes = [vp, vp, vp, fp, fp, i32, i32, i64, i64, i32, f32, i64, i32, vp]
     lib.pda_attn_fwd_variant.restype = i32
     lib.pda_attn_tail_plan.argtypes = [i32, i32, i64, i64, i32, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32),
-                                       C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+                                       C.POINTER(i64), C.POINTER(i64)]
     lib.pda_attn_tail_plan.restype = i32
     lib.pda_attn_merge.argtypes = [C.POINTER(vp), C.POINTER(vp), i32, fp, fp, i64, i32, vp]
     lib.pda_attn_merge.restype = i32
@@ -167,12 +168,14 @@ def attn_fwd_variant(q, k, v, out, lse, scale: float, variant: int, kv_valid_len
 
 
 def attn_tail_plan(B: int, H: int, Sq: int, kv_valid_len: int, d: int, n_cu: int = 0):
-    """pda_attn_tail_plan: dict(n_tiles, n_cut, split, first_keys, part_keys, workspace_slots); n_cu = 0 asks the current device."""
-    a, b, c, e, f, g = C.c_int64(0), C.c_int64(0), C.c_int(0), C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    """pda_attn_tail_plan: dict(n_tiles, n_cut, split, part_offsets, workspace_slots); part_offsets lists the
+    split + 1 boundaries of the key ranges of a cut tile ([] if nothing is cut); n_cu = 0 asks the current device."""
+    a, b, c, f = C.c_int64(0), C.c_int64(0), C.c_int(0), C.c_int64(0)
+    offs = (C.c_int64 * (PDA_MAX_KEY_RANGES + 1))()
     _check(lib.pda_attn_tail_plan(int(B), int(H), int(Sq), int(kv_valid_len), int(d), int(n_cu),
-                                  C.byref(a), C.byref(b), C.byref(c), C.byref(e), C.byref(f), C.byref(g)))
-    return {"n_tiles": a.value, "n_cut": b.value, "split": c.value, "first_keys": g.value, "part_keys": e.value,
-            "workspace_slots": f.value}
+                                  C.byref(a), C.byref(b), C.byref(c), offs, C.byref(f)))
+    return {"n_tiles": a.value, "n_cut": b.value, "split": c.value,
+            "part_offsets": [offs[j] for j in range(c.value + 1)] if c.value > 1 else [], "workspace_slots": f.value}
 
 
 def attn_fwd_bf16out(q, k, v, out, lse, scale: float, kv_valid_len: Optional[int] = None, stream=None):

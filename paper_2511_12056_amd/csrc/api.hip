@@ -351,8 +351,7 @@ int pda_attn_fwd_variant(const void* q, const void* k, const void* v, float* out
 }
 
 int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
-                       int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_keys, int64_t* workspace_slots,
-                       int64_t* first_keys) {
+                       int64_t* n_tiles, int64_t* n_cut, int* split, int64_t* part_offsets, int64_t* workspace_slots) {
     if (B < 0 || H < 0 || Sq < 0 || kv_valid_len < 0) return fail(PDA_ERR_INVALID_ARG, "negative size");
     if (d != 64 && d != 128) return fail(PDA_ERR_UNSUPPORTED, "head dim d=%d not supported (64 or 128)", d);
     if ((int64_t)B * H > 65535) return fail(PDA_ERR_UNSUPPORTED, "B*H > 65535");
@@ -367,8 +366,8 @@ int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, in
     if (n_tiles) *n_tiles = t.n_tiles;
     if (n_cut) *n_cut = t.n_cut;
     if (split) *split = t.split;
-    if (part_keys) *part_keys = t.part_keys;
-    if (first_keys) *first_keys = t.first_keys;
+    if (part_offsets)
+        for (int j = 0; j <= PDA_MAX_KEY_RANGES; ++j) part_offsets[j] = t.split > 1 ? t.part_off[j] : (j == 0 ? 0 : kv_valid_len);
     if (workspace_slots) *workspace_slots = pda::tail_slots(t, false);
     return PDA_OK;
 }

@@ -145,11 +145,10 @@ __global__ __launch_bounds__(512 / NQ, 1) void attn_fwd_sp_kernel(const AttnPara
     const int q_tile = tile - bh * p.tiles_per_head;
     const int b = bh / p.Hg, h = bh - b * p.Hg;
     // this item's key range [kv0, kv1) (tile aligned): all keys, or range `part` of a cut tile
-    const int64_t kv0 = part == 0 ? 0 : p.first_keys + (part - 1) * p.part_keys;
-    int64_t kv1 = p.n_v;
+    int64_t kv0 = 0, kv1 = p.n_v;
     if (p.split > 1 && tile >= p.n_full) {
-        const int64_t e1 = part == 0 ? p.first_keys : kv0 + p.part_keys;
-        if (e1 < p.n_v) kv1 = e1;
+        kv0 = p.part_off[part];
+        kv1 = p.part_off[part + 1];
     }
     const __bf16* __restrict__ qp = p.q + (int64_t)b * p.q_bs + (int64_t)h * p.q_hs;
     const __bf16* __restrict__ kp = p.k + (int64_t)b * p.kv_bs + (int64_t)h * p.kv_hs + kv0 * D;
@@ -702,14 +701,16 @@ static hipError_t launch_sp(AttnParams p, int BH, float* ws, int64_t ws_slots, h
     const int64_t slots = tail_slots(t, p.out_bf16 != 0);
     if (ws == nullptr || slots > ws_slots) return hipErrorInvalidValue;
     // no key range may be empty or start off a 64-key boundary
-    if (t.split > 1 && (t.first_keys < 64 || t.part_keys < 64 || (t.first_keys | t.part_keys) % 64 != 0 ||
-                        t.first_keys + (int64_t)(t.split - 2) * t.part_keys >= p.n_v)) return hipErrorInvalidValue;
+    if (t.split > 1) {
+        if (t.split > kMaxSplit || t.part_off[0] != 0 || t.part_off[t.split] != p.n_v) return hipErrorInvalidValue;
+        for (int j = 0; j < t.split; ++j)
+            if (t.part_off[j + 1] <= t.part_off[j] || t.part_off[j] % 64 != 0) return hipErrorInvalidValue;
+    }
     p.tiles_per_head = t.tiles_per_head;
     p.split = t.split;
     p.n_cut = (int)t.n_cut;
     p.n_full = (int)(t.n_tiles - t.n_cut);
-    p.part_keys = t.part_keys;
-    p.first_keys = t.first_keys;
+    for (int j = 0; j <= kMaxSplit; ++j) p.part_off[j] = t.part_off[j];
     p.part_out = slots ? ws : nullptr;
     p.part_lse = slots ? ws + slots * (M * D) : nullptr;
     p.counter = reinterpret_cast<int*>(ws + ws_slots * kSlotFloats);     // two ints behind the slots, zero between launches

@@ -49,16 +49,14 @@ struct AttnParams {
     float scale_log2e;      // scale * log2(e)
     // Work items of the software-pipelined kernel, taken in index order by persistent workgroups.
     // Items [0, n_full) are whole 256-row query tiles (tile = item; head = tile / tiles_per_head).
-    // Every later tile is cut into `split` key ranges, the first of first_keys keys, the others of
-    // part_keys keys (the last one: what is left), one item each (item = n_full + part * n_cut +
-    // cut tile), so that the end of the launch is made of short items;
+    // Every later tile is cut into `split` key ranges [part_off[j], part_off[j+1]), one item each
+    // (item = n_full + part * n_cut + cut tile), so that the end of the launch is made of short items;
     // part 0 writes out/lse, parts >= 1 write normalised partials to part_out/part_lse, which a
     // merge pass folds into out/lse.  split <= 1: no cut.
     int tiles_per_head;
     int n_full;
     int split;
-    int64_t part_keys;
-    int64_t first_keys;
+    int64_t part_off[17];   // first key of each range (multiples of 64); part_off[split] = n_v
     float* part_out;        // [(tile - n_full) * (split - 1) + part - 1][256][d]
     float* part_lse;        // [(tile - n_full) * (split - 1) + part - 1][256]
     int n_cut;              // number of cut tiles (the last n_cut of the launch)
@@ -96,6 +94,13 @@ struct AttnParams {
 // A = k / (k + split - 1) (both kinds of CU then finish together), split = 4 after one round of
 // whole tiles, else 3, within the workspace cap and with short ranges of at least 1024 keys
 // (measured, one head at S = 119 056 = 256 + 210 tiles: 5.78 -> 5.47 ms; 5 x 36 000: 2.64 -> 2.55).
+// After four or more rounds of whole tiles the CUs do not become free together, items are handed
+// out as CUs ask for them, and what is left idle at the end is about half of the items started
+// last.  There the ranges (2 to 6 of them) get DECREASING sizes, each 5/8 of the one before, range
+// 0 first: the items started last are the shortest (measured, 3-head group at S = 119 056, five
+// ranges of 41 / 26 / 16 / 10 / 6 % instead of 20 % each: 16.53 -> 16.43 ms; 6 heads, three
+// ranges of 50 / 31 / 19 %: 32.98 -> 32.85 ms); kept equal if the last range would fall under
+// 50 key tiles.
 // A pure function of (Sq, number of (batch, head) pairs, valid keys, CU count): the cut tiles are
 // the last n_cut of the launch's n_tiles tiles in (batch, head, query tile) order.
 constexpr int kMaxSplit = 16;
@@ -104,8 +109,8 @@ struct TailPlan {
     int64_t n_tiles;
     int64_t n_cut;          // 0 if no tile is cut
     int split;              // 1 if no tile is cut
-    int64_t part_keys;      // keys of ranges 1 .. split-1 (multiple of 64; the last range holds what is left); 0 if no tile is cut
-    int64_t first_keys;     // keys of range 0 (multiple of 64); equal to part_keys unless the cut is unequal
+    int64_t part_off[kMaxSplit + 1];   // range j of a cut tile = keys [part_off[j], part_off[j+1]); multiples of 64 up to
+                                       // part_off[split] = n_v; entries beyond split are n_v as well
 };
 inline int64_t max_extra_slots(int n_cu) { return (int64_t)n_cu * 9 / 4; }
 inline int64_t part_keys_for(int64_t n_v, int s) { return ((n_v + s - 1) / s + 63) / 64 * 64; }
@@ -115,13 +120,14 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
     t.n_tiles = (int64_t)t.tiles_per_head * BH;
     t.split = 1;
     const int64_t rem = t.n_tiles % n_cu;
+    bool one_round = false;
     if (rem) {
         const int64_t nt = (n_v + 63) / 64;
         // One round of parts (n_cu / rem ranges per tile) where the parts are short and start together:
         // a launch of fewer tiles than CUs, or sweeps of under 200 key tiles whose left-over tiles
         // fill at most half the machine.  Otherwise about three rounds of parts, round(3 n_cu / rem),
         // of at least 100 key tiles each (at least 50 where that gives no more than 4 ranges).
-        const bool one_round = t.n_tiles < n_cu || (nt < 200 && 2 * rem <= n_cu);
+        one_round = t.n_tiles < n_cu || (nt < 200 && 2 * rem <= n_cu);
         int64_t s_max = kMaxSplit;
         if (!one_round) {
             int64_t by_len = nt / 50 < 4 ? nt / 50 : 4;
@@ -136,10 +142,27 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
         while (s >= 2 && (s - 1) * part_keys_for(n_v, (int)s) >= n_v) --s;   // the last range must not be empty
         if (s >= 2) t.split = (int)s;
     }
+    for (int j = 0; j <= kMaxSplit; ++j) t.part_off[j] = n_v;
     if (t.split > 1) {
         t.n_cut = rem;
-        t.part_keys = part_keys_for(n_v, t.split);
-        t.first_keys = t.part_keys;
+        const int64_t pk = part_keys_for(n_v, t.split);
+        for (int j = 0; j < t.split; ++j) t.part_off[j] = j * pk;
+        // decreasing ranges after four or more rounds of whole tiles: weights 8^(s-1-j) 5^j
+        if (!one_round && t.n_tiles >= 4 * (int64_t)n_cu && t.split <= 6) {
+            int64_t w[6], total = 0, cum = 0, off[7];
+            for (int j = 0; j < t.split; ++j) {
+                w[j] = 1;
+                for (int i = 0; i < t.split - 1 - j; ++i) w[j] *= 8;
+                for (int i = 0; i < j; ++i) w[j] *= 5;
+                total += w[j];
+            }
+            off[0] = 0;
+            for (int j = 1; j < t.split; ++j) { cum += w[j - 1]; off[j] = n_v * cum / total / 64 * 64; }
+            off[t.split] = n_v;
+            bool ok = n_v - off[t.split - 1] >= 3200;
+            for (int j = 0; j < t.split; ++j) ok = ok && off[j + 1] > off[j];
+            if (ok) for (int j = 0; j < t.split; ++j) t.part_off[j] = off[j];
+        }
     }
     // unequal cut: many left-over tiles after at most three rounds of whole tiles
     if (rem && 2 * rem > n_cu && t.n_tiles < 4 * (int64_t)n_cu && t.n_tiles > n_cu) {
@@ -153,8 +176,7 @@ inline TailPlan plan_tail(int64_t Sq, int BH, int64_t n_v, int n_cu) {
             if (part < 1024 || first + (s - 2) * part >= n_v) continue;    // short ranges too short, or the last one empty
             t.split = (int)s;
             t.n_cut = rem;
-            t.first_keys = first;
-            t.part_keys = part;
+            for (int j = 0; j <= kMaxSplit; ++j) t.part_off[j] = j == 0 ? 0 : (j < s ? first + (j - 1) * part : n_v);
             break;
         }
     }

@@ -235,38 +235,48 @@ def test_tail_plan_matches_the_rule_restated_in_python(pda):
         got = pda.attn_tail_plan(1, BH, Sq, n_v, d, n_cu)
         want = tail_plan(BH, Sq, n_v, d, n_cu)
         assert got == want, (n_cu, BH, Sq, n_v, d, got, want)
-    # the workloads: one 3-head group at 720p is 1 398 tiles = 5 x 256 + 118; round(768/118) = 7 ranges, 5 fit the workspace
+    # the workloads: one 3-head group at 720p is 1 398 tiles = 5 x 256 + 118; round(768/118) = 7 ranges, 5 fit the
+    # workspace; after five rounds of whole tiles the ranges decrease by 5/8 each (41 / 26 / 16 / 10 / 6 % of the keys)
     assert pda.attn_tail_plan(1, 3, 119056, 119056, 128, 256) == {
-        "n_tiles": 1398, "n_cut": 118, "split": 5, "first_keys": 23872, "part_keys": 23872, "workspace_slots": 472}
+        "n_tiles": 1398, "n_cut": 118, "split": 5, "part_offsets": [0, 49344, 80192, 99456, 111488, 119056], "workspace_slots": 472}
+    # six heads at 720p: 2 796 tiles = 10 x 256 + 236, three ranges of 50 / 31 / 19 %
+    assert pda.attn_tail_plan(1, 6, 119056, 119056, 128, 256) == {
+        "n_tiles": 2796, "n_cut": 236, "split": 3, "part_offsets": [0, 59008, 95936, 119056], "workspace_slots": 472}
     # 24 heads x 9 600: 912 tiles = 3 x 256 + 144 (more than half a round): a long first range for 144 CUs,
     # two short ones that the other 112 work off three each: A = 3/5 of the keys plus 1 %
     assert pda.attn_tail_plan(1, 24, 9600, 9600, 128, 256) == {
-        "n_tiles": 912, "n_cut": 144, "split": 3, "first_keys": 5888, "part_keys": 1856, "workspace_slots": 288}
+        "n_tiles": 912, "n_cut": 144, "split": 3, "part_offsets": [0, 5888, 7744, 9600], "workspace_slots": 288}
     # one head at 720p: 466 tiles = 256 + 210: k = ceil(420 / 46) = 10, A = 10/12
     assert pda.attn_tail_plan(1, 1, 119056, 119056, 128, 256) == {
-        "n_tiles": 466, "n_cut": 210, "split": 3, "first_keys": 100416, "part_keys": 9344, "workspace_slots": 420}
-    # 10 heads x 9 600: 380 tiles = 256 + 124 short ones: one round of 248 parts
+        "n_tiles": 466, "n_cut": 210, "split": 3, "part_offsets": [0, 100416, 109760, 119056], "workspace_slots": 420}
+    # 10 heads x 9 600: 380 tiles = 256 + 124 short ones: one round of 248 equal parts
     assert pda.attn_tail_plan(1, 10, 9600, 9600, 128, 256) == {
-        "n_tiles": 380, "n_cut": 124, "split": 2, "first_keys": 4800, "part_keys": 4800, "workspace_slots": 124}
+        "n_tiles": 380, "n_cut": 124, "split": 2, "part_offsets": [0, 4800, 9600], "workspace_slots": 124}
+    # 30 heads x 9 600: four rounds of whole tiles, but short sweeps: one round of equal parts, not decreasing ones
+    assert pda.attn_tail_plan(1, 30, 9600, 9600, 128, 256)["part_offsets"] == [0, 4800, 9600]
     # 24 heads x 4 800: 456 tiles = 256 + 200 of 75 key tiles: left uncut
-    assert pda.attn_tail_plan(1, 24, 4800, 4800, 128, 256)["split"] == 1
-    # one head group of the 544 x 960 clip: 792 tiles = 3 x 256 + 24, 1 055 key tiles: at most 10 ranges
+    assert pda.attn_tail_plan(1, 24, 4800, 4800, 128, 256) == {
+        "n_tiles": 456, "n_cut": 0, "split": 1, "part_offsets": [], "workspace_slots": 0}
+    # one head group of the 544 x 960 clip: 792 tiles = 3 x 256 + 24, 1 055 key tiles: 10 equal ranges
     assert pda.attn_tail_plan(1, 3, 67576, 67476, 128, 256) == {
-        "n_tiles": 792, "n_cut": 24, "split": 10, "first_keys": 6784, "part_keys": 6784, "workspace_slots": 216}
-    # no plan needs more than 9/4 slots per compute unit for the parts beyond the first, and no range is empty
-    for t in range(1, 1025):
-        for n_v in (1 << 20, 12800, 8200, 8193, 51200 + t):
+        "n_tiles": 792, "n_cut": 24, "split": 10, "part_offsets": [6784 * j for j in range(10)] + [67476], "workspace_slots": 216}
+    # no plan needs more than 9/4 slots per compute unit for the parts beyond the first; the ranges of every plan
+    # start at 0, end at n_v, are not empty and begin at multiples of 64
+    for t in range(1, 1400):
+        for n_v in (1 << 20, 12800, 8200, 8193, 51200 + t, 3300 + 7 * t):
             pl = pda.attn_tail_plan(1, 1, 256 * t, n_v, 128, 256)
             assert pl["workspace_slots"] <= 576
-            assert pl["split"] == 1 or (pl["first_keys"] >= 64 and pl["first_keys"] + (pl["split"] - 2) * pl["part_keys"] < n_v)
-            assert pl["first_keys"] % 64 == 0 and pl["part_keys"] % 64 == 0
+            if pl["split"] > 1:
+                o = pl["part_offsets"]
+                assert len(o) == pl["split"] + 1 and o[0] == 0 and o[-1] == n_v, (t, n_v, pl)
+                assert all(b > a for a, b in zip(o, o[1:])) and all(a % 64 == 0 for a in o[:-1]), (t, n_v, pl)
     # a launch of fewer tiles than compute units: one head of the 9 600-token clip is 38 tiles, 256 // 38 = 6 ranges each
     assert pda.attn_tail_plan(1, 1, 9600, 9600, 128, 256) == {
-        "n_tiles": 38, "n_cut": 38, "split": 6, "first_keys": 1600, "part_keys": 1600, "workspace_slots": 190}
+        "n_tiles": 38, "n_cut": 38, "split": 6, "part_offsets": [1600 * j for j in range(7)], "workspace_slots": 190}
     # the tiny workload (d = 64): 8 tiles, 1 024 keys allow two ranges of 512
     assert pda.attn_tail_plan(1, 2, 1024, 1024, 64, 256) == {
-        "n_tiles": 8, "n_cut": 8, "split": 2, "first_keys": 512, "part_keys": 512, "workspace_slots": 8}
+        "n_tiles": 8, "n_cut": 8, "split": 2, "part_offsets": [0, 512, 1024], "workspace_slots": 8}
     # an empty key set is never cut
     assert pda.attn_tail_plan(1, 3, 5000, 0, 128, 256)["n_cut"] == 0
-    assert pda.lib.pda_attn_tail_plan(1, 1, 8, 8, 32, 256, None, None, None, None, None, None) == 2
-    assert pda.lib.pda_attn_tail_plan(1, 1, -1, 8, 128, 256, None, None, None, None, None, None) == 1
+    assert pda.lib.pda_attn_tail_plan(1, 1, 8, 8, 32, 256, None, None, None, None, None) == 2
+    assert pda.lib.pda_attn_tail_plan(1, 1, -1, 8, 128, 256, None, None, None, None, None) == 1

@@ -305,7 +305,8 @@ def test_unequal_key_ranges(d):
     B, H, Sq, Skv, n_v = 1, 20, 5200, 13100, 13050
     plan = pda.attn_tail_plan(B, H, Sq, n_v, d)
     if torch.cuda.get_device_properties(0).multi_processor_count == 256:
-        assert plan["n_cut"] == 164 and plan["split"] == 4 and plan["first_keys"] > 2 * plan["part_keys"], plan
+        o = plan["part_offsets"]
+        assert plan["n_cut"] == 164 and plan["split"] == 4 and o[1] - o[0] > 2 * (o[2] - o[1]), plan
     qb, kb, vb = gen_qkv(4242, B, H, Sq, Skv, d, unit_rms=True)
     o, l = _run(qb, kb, vb, d ** -0.5, n_v)
     rng = np.random.default_rng(3)
@@ -313,6 +314,33 @@ def test_unequal_key_ranges(d):
         rows = np.unique(np.concatenate([[0, 255, 256, Sq - 1], rng.choice(Sq, size=120, replace=False)]))
         ro, rl = attention_head(qb[0, h], kb[0, h], vb[0, h], d ** -0.5, n_v, rows=rows)
         assert_close(o[0, h][rows], l[0, h][rows], ro, rl, f"unequal ranges, d = {d}, head {h}")
+
+
+def test_decreasing_key_ranges():
+    """A launch of four rounds of whole tiles plus 16 left-over tiles cuts those into key ranges of
+    decreasing size (each 5/8 of the one before); sampled rows of whole and of cut tiles of the
+    last head, masked tail inside the last range, against the oracle.  (The 26 heads repeat four
+    generated ones.)"""
+    import torch
+    import paper_2511_12056_amd as pda
+    from oracle import attention_head
+    B, H, Sq, Skv, n_v, d = 1, 26, 10100, 31100, 31000, 128
+    plan = pda.attn_tail_plan(B, H, Sq, n_v, d)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        o = plan["part_offsets"]
+        assert plan["n_tiles"] == 1040 and plan["n_cut"] == 16 and plan["split"] == 4, plan
+        assert o[1] - o[0] > o[2] - o[1] > o[3] - o[2] > o[4] - o[3] >= 3200, plan
+    q4, k4, v4 = gen_qkv(808, B, 4, Sq, Skv, d, unit_rms=True)
+    idx = np.arange(H) % 4
+    qb, kb, vb = q4[:, idx], k4[:, idx], v4[:, idx]
+    o, l = _run(qb, kb, vb, d ** -0.5, n_v)
+    rng = np.random.default_rng(5)
+    for h in (0, 25):                       # head 25: tiles 0-23 whole, tiles 24-39 (rows 6144..) cut (256 CUs)
+        rows = np.unique(np.concatenate([[0, 6143, 6144, 6400, Sq - 1], rng.choice(Sq, size=150, replace=False)]))
+        ro, rl = attention_head(qb[0, h], kb[0, h], vb[0, h], d ** -0.5, n_v, rows=rows)
+        assert_close(o[0, h][rows], l[0, h][rows], ro, rl, f"decreasing ranges, head {h}")
+    # the same rows of equal heads agree bit for bit where both lie in whole tiles
+    assert np.array_equal(o[0, 1, :6144], o[0, 25, :6144]) and np.array_equal(l[0, 1, :6144], l[0, 25, :6144])
 
 
 @pytest.mark.parametrize("B,H,Sq,Skv,n_v,all_cut,d", [(1, 24, 700, 12900, 12850, True, 128),  # 72 tiles, every one cut in three

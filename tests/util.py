@@ -49,17 +49,17 @@ def assert_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
 
 
 def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
-    """Which query tiles an attention launch (d = 64 or 128) computes as merged key-range partials: the rule
-    of pda_attn_tail_plan written out independently.  Tiles of 256 rows; the rem = n_tiles mod n_cu
-    tiles that do not fill a round of whole tiles are cut into s = round(3*n_cu/rem) key ranges,
-    at least 2 and at most min(16, L, n_v // 512, 1 + (9*n_cu//4) // rem) with nt the key tiles (of
-    64) of a whole sweep and L = max(nt // 100, min(nt // 50, 4)), lowered until the last range is
-    not empty; uncut if that leaves less than 2.  A launch of fewer tiles than compute units, or one
-    with nt < 200 whose left-over tiles fill at most half the machine, is cut so that one round of
-    parts fills the machine instead: s = n_cu // rem under the same caps except L.  A range holds
-    ceil(n_v / s) keys rounded up to a multiple of 64 (first_keys = part_keys), except in the
-    unequal cut described at the end of the function."""
-    plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "first_keys": 0, "part_keys": 0, "workspace_slots": 0}
+    """Which query tiles an attention launch (d = 64 or 128) computes as merged key-range partials, and
+    over which key ranges: the rule of pda_attn_tail_plan written out independently.  Tiles of 256
+    rows; the rem = n_tiles mod n_cu tiles that do not fill a round of whole tiles are cut into s =
+    round(3*n_cu/rem) key ranges, at least 2 and at most min(16, L, n_v // 512, 1 + (9*n_cu//4) //
+    rem) with nt the key tiles (of 64) of a whole sweep and L = max(nt // 100, min(nt // 50, 4)),
+    lowered until the last range is not empty; uncut if that leaves less than 2.  A launch of fewer
+    tiles than compute units, or one with nt < 200 whose left-over tiles fill at most half the
+    machine, is cut so that one round of parts fills the machine instead: s = n_cu // rem under the
+    same caps except L.  Ranges are equal, ceil(n_v / s) keys rounded up to a multiple of 64, except
+    (a) decreasing ranges and (b) a long first range, both described where they are computed."""
+    plan = {"n_tiles": 0, "n_cut": 0, "split": 1, "part_offsets": [], "workspace_slots": 0}
     if d not in (64, 128) or n_v <= 0 or BH * Sq <= 0:
         return plan
     tiles = -(-Sq // 256) * BH
@@ -72,7 +72,8 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     def keys(s):
         return -(-(-(-n_v // s)) // 64) * 64
 
-    if tiles < n_cu or (nt < 200 and 2 * rem <= n_cu):   # short parts that start together: one round of parts
+    one_round = tiles < n_cu or (nt < 200 and 2 * rem <= n_cu)   # short parts that start together
+    if one_round:
         s_max = min(16, n_v // 512, 1 + (9 * n_cu // 4) // rem)
         s = min(n_cu // rem, s_max)
     else:
@@ -82,10 +83,19 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
     while s >= 2 and (s - 1) * keys(s) >= n_v:
         s -= 1
     if s >= 2:
-        plan.update(n_cut=rem, split=s, first_keys=keys(s), part_keys=keys(s), workspace_slots=rem * (s - 1))
-    # Unequal cut where the left-over tiles fill more than half the machine after one to three rounds
-    # of whole tiles: a long first range (a fraction k / (k + s - 1) of the keys plus 1 %, up to the
-    # next multiple of 64) and s - 1 short ones of at least 1024 keys, k = ceil(rem (s-1) / (n_cu - rem));
+        offs = [j * keys(s) for j in range(s)] + [n_v]
+        # (a) After four or more rounds of whole tiles (and at most 6 ranges): decreasing ranges, each 5/8
+        # of the one before, boundaries rounded down to multiples of 64; kept equal if the last range
+        # would hold fewer than 3200 keys or a range would be empty.
+        if not one_round and tiles >= 4 * n_cu and s <= 6:
+            w = [8 ** (s - 1 - j) * 5 ** j for j in range(s)]
+            dec = [0] + [n_v * sum(w[:j]) // sum(w) // 64 * 64 for j in range(1, s)] + [n_v]
+            if n_v - dec[s - 1] >= 3200 and all(b > a for a, b in zip(dec, dec[1:])):
+                offs = dec
+        plan.update(n_cut=rem, split=s, part_offsets=offs, workspace_slots=rem * (s - 1))
+    # (b) Where the left-over tiles fill more than half the machine after one to three rounds of whole
+    # tiles: a long first range (a fraction k / (k + s - 1) of the keys plus 1 %, up to the next
+    # multiple of 64) and s - 1 short ones of at least 1024 keys, k = ceil(rem (s-1) / (n_cu - rem));
     # s = 4 after one round of whole tiles, else 3, within the workspace cap, lowered until it fits.
     if 2 * rem > n_cu and n_cu < tiles < 4 * n_cu:
         s = min(4 if tiles < 2 * n_cu else 3, 1 + (9 * n_cu // 4) // rem)
@@ -94,7 +104,8 @@ def tail_plan(BH: int, Sq: int, n_v: int, d: int, n_cu: int):
             first = ((n_v * k // (k + s - 1) + n_v // 100) // 64 + 1) * 64
             part = -(-(-(-(n_v - first) // (s - 1))) // 64) * 64 if first < n_v else 0
             if first < n_v and part >= 1024 and first + (s - 2) * part < n_v:
-                plan.update(n_cut=rem, split=s, first_keys=first, part_keys=part, workspace_slots=rem * (s - 1))
+                plan.update(n_cut=rem, split=s, part_offsets=[0] + [first + j * part for j in range(s - 1)] + [n_v],
+                            workspace_slots=rem * (s - 1))
                 break
             s -= 1
     return plan
