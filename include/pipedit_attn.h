@@ -131,17 +131,18 @@ int pda_attn_fwd_noalloc(const void* q, const void* k, const void* v, float* out
  * (in (batch, head, query tile) order: the partly filled last round; all tiles of a launch
  * with fewer tiles than compute units; none where the key ranges would get too short to pay)
  * are each computed as `split` (2..PDA_MAX_KEY_RANGES) partial attentions over consecutive key
- * ranges (range j = keys [part_offsets[j], part_offsets[j+1]), boundaries at multiples of 64;
- * equal ranges, or a long first one and short others where many left-over tiles follow few rounds
- * of whole tiles, or decreasing ones after many rounds, whichever balances the end of the launch
- * better) and merged with the formula of pda_attn_merge; all other tiles are swept in one pass.  Hence two launches agree bit for bit
- * on every row that lies in an uncut tile of both, and to the rounding of the probabilities on
- * the others.  n_cu: compute units of the device (0 = ask the current device).  Outputs (any may
- * be NULL): n_tiles, n_cut (0 = nothing is cut), split (1 = nothing is cut), part_offsets (HOST
- * array of PDA_MAX_KEY_RANGES + 1 values: part_offsets[0] = 0, entries from index split on are
- * kv_valid_len), and
- * workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32 out; never more
- * than 9/4 per compute unit; a d = 64 launch fills half of each slot).  Empty key sets are never cut.
+ * ranges, range j = keys [part_offsets[j], part_offsets[j+1]) with boundaries at multiples of 64,
+ * and merged with the formula of pda_attn_merge; all other tiles are swept in one pass.  The
+ * ranges are equal, or a long first one and short others (many left-over tiles after one to three
+ * rounds of whole tiles), or of decreasing size (after four or more rounds), whichever balances
+ * the end of the launch better.  Hence two launches agree bit for bit on every row that lies in
+ * an uncut tile of both, and to the rounding of the probabilities on the others.
+ * n_cu: compute units of the device (0 = ask the current device).  Outputs (any may be NULL):
+ * n_tiles; n_cut (0 = nothing is cut); split (1 = nothing is cut); part_offsets, a HOST array of
+ * PDA_MAX_KEY_RANGES + 1 values (part_offsets[0] = 0, entries from index split on are
+ * kv_valid_len); workspace_slots, the number of 132 096-byte partial slots the launch uses (fp32
+ * out; never more than 9/4 per compute unit; a d = 64 launch fills half of each slot).  Empty key
+ * sets are never cut.
  */
 #define PDA_MAX_KEY_RANGES 16
 int pda_attn_tail_plan(int B, int H, int64_t Sq, int64_t kv_valid_len, int d, int n_cu,
