@@ -317,7 +317,7 @@ extern "C" {
 
 const char* pda_last_error(void) { return g_err; }
 
-int pda_version(void) { return 300; }
+int pda_version(void) { return 310; }
 
 int pda_attn_fwd(const void* q, const void* k, const void* v, float* out, float* lse,
                  int B, int H, int64_t Sq, int64_t Skv, int d, float scale,
